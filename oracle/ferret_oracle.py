@@ -1,0 +1,196 @@
+"""Python face of the CPU oracle (oracle/ferret_oracle.c) -- TEST INFRASTRUCTURE ONLY.
+
+Only tests, the smoke check and the benchmark's cpu_baseline leg may import this module.
+It compiles the C file with gcc on first use and calls it through ctypes.  Nothing here
+touches the HIP library or shares code with it.
+
+The oracle works on one pipeline stage at a time, on the plain problem statement of
+Alg. 1 (paper, appendix "Algorithm Details"): the stale gradient, the tau+1 stored
+versions oldest first, lambda, eta.  `OracleRing` adds the bookkeeping of a version store
+across several optimisation steps (Sec. "Fine-grained Pipeline Parallelism", T2: a stage
+keeps a bounded number of versions) so that multi-step behaviour can be checked.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "ferret_oracle.c")
+_LIB = os.path.join(_HERE, "libferret_oracle.so")
+_lib = None
+
+ITERS_FULL = -1
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle (gcc, -O2, no fast-math, no FMA contraction)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
+               "-fno-fast-math", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        pp = ctypes.POINTER(ctypes.c_void_p)
+        lib.ferret_oracle_effective_iters.restype = ctypes.c_int32
+        lib.ferret_oracle_effective_iters.argtypes = [ctypes.c_int32, ctypes.c_int32]
+        lib.ferret_oracle_segment_boundary.restype = ctypes.c_int32
+        lib.ferret_oracle_segment_boundary.argtypes = [ctypes.c_int32] * 3
+        lib.ferret_oracle_bf16_to_f32.restype = ctypes.c_float
+        lib.ferret_oracle_bf16_to_f32.argtypes = [ctypes.c_uint16]
+        lib.ferret_oracle_f32_to_bf16.restype = ctypes.c_uint16
+        lib.ferret_oracle_f32_to_bf16.argtypes = [ctypes.c_float]
+        lib.ferret_oracle_stage_f32.restype = ctypes.c_int
+        lib.ferret_oracle_stage_f32.argtypes = [
+            ctypes.c_int64, ctypes.c_int32, pp, ctypes.c_void_p, ctypes.c_int32,
+            ctypes.c_double, ctypes.c_double, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_void_p, ctypes.c_int32]
+        lib.ferret_oracle_stage_bf16.restype = ctypes.c_int
+        lib.ferret_oracle_stage_bf16.argtypes = [
+            ctypes.c_int64, ctypes.c_int32, pp, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_int32, ctypes.c_double, ctypes.c_double, ctypes.c_void_p,
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32]
+        _lib = lib
+    return _lib
+
+
+# ---- small scalar helpers ---------------------------------------------------------------
+def effective_iters(K: int, tau: int) -> int:
+    return int(_load().ferret_oracle_effective_iters(K, tau))
+
+
+def segment_boundaries(tau: int, K: int) -> List[int]:
+    """[s_0 .. s_K'] for staleness tau and iteration count K (empty loop -> [0] or [tau])."""
+    Kp = effective_iters(K, tau)
+    if Kp == 0:
+        return [tau]
+    return [int(_load().ferret_oracle_segment_boundary(i, tau, Kp)) for i in range(Kp + 1)]
+
+
+def bf16_bits_to_f32(bits: int) -> float:
+    return float(_load().ferret_oracle_bf16_to_f32(bits))
+
+
+def f32_to_bf16_bits(x: float) -> int:
+    return int(_load().ferret_oracle_f32_to_bf16(np.float32(x)))
+
+
+# ---- array plumbing ---------------------------------------------------------------------
+def _as_np(a, dtype) -> np.ndarray:
+    """torch tensor / numpy array -> contiguous numpy array of `dtype` (no value change)."""
+    if hasattr(a, "detach"):               # torch tensor
+        import torch
+        t = a.detach().cpu().contiguous()
+        if t.dtype == torch.bfloat16:
+            t = t.view(torch.int16)
+        a = t.numpy()
+    a = np.ascontiguousarray(a)
+    if dtype == np.uint16 and a.dtype == np.int16:
+        a = a.view(np.uint16)
+    if a.dtype != dtype:
+        raise TypeError(f"expected {dtype}, got {a.dtype}")
+    return a
+
+
+def _ptr_array(arrs: Sequence[np.ndarray]):
+    P = (ctypes.c_void_p * len(arrs))(*[a.ctypes.data for a in arrs])
+    return P
+
+
+def compensate_stage_f32(versions, g0, K: int, lam: float, eta: float, n_threads: int = 1,
+                         want_g: bool = True):
+    """One stage, fp32 storage.  versions: tau+1 arrays oldest first.
+    Returns (theta_new float32[n], g_K' float64[n] or None, norms float64[3])."""
+    V = [_as_np(v, np.float32) for v in versions]
+    g = _as_np(g0, np.float32)
+    n = g.size
+    for v in V:
+        if v.size != n:
+            raise ValueError("version/gradient size mismatch")
+    out = np.empty(n, np.float32)
+    g_out = np.empty(n, np.float64) if want_g else None
+    norms = np.zeros(3, np.float64)
+    rc = _load().ferret_oracle_stage_f32(
+        n, len(V), _ptr_array(V), g.ctypes.data, K, float(lam), float(eta), out.ctypes.data,
+        g_out.ctypes.data if want_g else None, norms.ctypes.data, n_threads)
+    if rc != 0:
+        raise ValueError("ferret_oracle_stage_f32: bad arguments")
+    return out, g_out, norms
+
+
+def compensate_stage_bf16(versions, g0, master, K: int, lam: float, eta: float,
+                          n_threads: int = 1, want_g: bool = True):
+    """One stage, bf16 versions/gradient (uint16 bit patterns or torch.bfloat16) + fp32 master.
+    Returns (theta_new uint16[n], master_new float32[n], g_K' float64[n] or None, norms)."""
+    V = [_as_np(v, np.uint16) for v in versions]
+    g = _as_np(g0, np.uint16)
+    m = _as_np(master, np.float32)
+    n = g.size
+    for v in V + [m]:
+        if v.size != n:
+            raise ValueError("size mismatch")
+    out = np.empty(n, np.uint16)
+    m_out = np.empty(n, np.float32)
+    g_out = np.empty(n, np.float64) if want_g else None
+    norms = np.zeros(3, np.float64)
+    rc = _load().ferret_oracle_stage_bf16(
+        n, len(V), _ptr_array(V), g.ctypes.data, m.ctypes.data, K, float(lam), float(eta),
+        out.ctypes.data, m_out.ctypes.data, g_out.ctypes.data if want_g else None,
+        norms.ctypes.data, n_threads)
+    if rc != 0:
+        raise ValueError("ferret_oracle_stage_bf16: bad arguments")
+    return out, m_out, g_out, norms
+
+
+# ---- version store across steps ---------------------------------------------------------
+class OracleRing:
+    """Per-stage store of the last R weight versions, plain Python lists.
+
+    step(j, g) applies Alg. 1 to stage j with effective staleness
+    min(tau_j, versions_held - 1) (during warm-up fewer than tau_j + 1 versions exist),
+    appends the new version and drops the oldest beyond R.
+    """
+
+    def __init__(self, staleness: Sequence[int], ring_depth: int, K: int, precision: str = "f32"):
+        self.tau = list(staleness)
+        self.R = int(ring_depth)
+        self.K = int(K)
+        self.precision = precision
+        self.versions: List[List[np.ndarray]] = [[] for _ in self.tau]
+        self.master: List[Optional[np.ndarray]] = [None for _ in self.tau]
+
+    def push(self, j: int, version, master=None) -> None:
+        dt = np.float32 if self.precision == "f32" else np.uint16
+        self.versions[j].append(_as_np(version, dt).copy())
+        if len(self.versions[j]) > self.R:
+            self.versions[j].pop(0)
+        if master is not None:
+            self.master[j] = _as_np(master, np.float32).copy()
+
+    def effective_tau(self, j: int) -> int:
+        return min(self.tau[j], len(self.versions[j]) - 1)
+
+    def step(self, j: int, g, lam: float, eta: float):
+        held = self.versions[j]
+        if not held:
+            raise RuntimeError("stage has no version yet")
+        tau = self.effective_tau(j)
+        window = held[len(held) - 1 - tau:]
+        if self.precision == "f32":
+            new, g_out, norms = compensate_stage_f32(window, g, self.K, lam, eta)
+            self.push(j, new)
+        else:
+            new, m_new, g_out, norms = compensate_stage_bf16(window, g, self.master[j], self.K,
+                                                              lam, eta)
+            self.push(j, new, m_new)
+        return new, g_out, norms
