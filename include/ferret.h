@@ -1,0 +1,215 @@
+/*
+ * ferret.h -- C ABI of libferret: iterative gradient compensation + weight update for
+ * pipelined online continual learning (Ferret), for AMD MI355X (gfx950).
+ *
+ * The operation (paper: Sec. "Iterative Gradient Compensation"; Alg. 1 "Iterative
+ * Gradients Compensation with lambda" in the appendix "Algorithm Details"):
+ * a pipeline stage j holds several versions of its parameters, because the gradient it
+ * receives was computed on weights that are tau_j updates old.  Before the update the
+ * stale gradient g is corrected with the weight drift accumulated since that version,
+ *
+ *     A_I(g, theta_new, theta_old) = g + lambda * g (.) g (.) (theta_new - theta_old)
+ *                                            (Eq. "gt-taylor-expansion-approximation")
+ *     g_{i+1} = A_I(g_i, V[s_{i+1}], V[s_i]),   i = 0 .. K'-1      (Alg. 1, iterative loop)
+ *     theta_next = V[tau] - eta * g_{K'}                            (Alg. 1, model update)
+ *
+ * where V[0] is the version the gradient was computed on and V[tau] the current one.
+ * Alg. 1 uses K' = tau and s_i = i.  With an iteration count K < tau the tau version
+ * steps are cut into K' = min(K, tau) contiguous segments, s_i = floor(i*tau/K').
+ *
+ * Memory model.  Every device buffer and the stream belong to the caller; the library
+ * allocates host memory only (inside the plan) and no device memory at all.  All device
+ * pointers must be 16-byte aligned.  Calls enqueue work on `hip_stream` and return
+ * without waiting; the returned status covers argument and launch errors only.
+ * A plan is not thread-safe: use it from one thread at a time.
+ *
+ * Layout (all offsets in ELEMENTS, all obtainable from the plan):
+ *   stage j      its tensors are laid end to end in model order, each starting at a
+ *                multiple of FERRET_ALIGN_ELEMS; n_j = padded element count.  Padding
+ *                elements take part in the arithmetic like any other element (keep them
+ *                zero: zero gradient and zero weight stay zero).
+ *   flat buffer  ("slot-shaped": grads, master, grad_out, src of push_version)
+ *                stage j occupies [flat_offset_j, flat_offset_j + n_j).
+ *   ring         stage-major: stage j owns an arena of ring_depth_j slots,
+ *                slot s of stage j = [ring_offset_j + s*slot_stride_j, ... + n_j).
+ *   storage type fp32 (FERRET_F32) or bf16 (FERRET_BF16_MASTER_F32) for ring and grads;
+ *                master, grad_out, src are always fp32.
+ *
+ * Errors: every function returning ferret_status returns FERRET_OK or a code below and
+ * leaves a message retrievable with ferret_last_error() (thread-local).  Nothing throws
+ * or aborts.
+ */
+#ifndef FERRET_H
+#define FERRET_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FERRET_MAX_STAGES 64       /* stages per plan (the stage table travels as a kernel argument) */
+#define FERRET_MAX_RING_DEPTH 4096
+#define FERRET_ALIGN_ELEMS 8       /* tensor start alignment inside a stage, in elements */
+#define FERRET_ITERS_FULL (-1)     /* n_iters: one iteration per version step (Alg. 1 literally) */
+#define FERRET_RING_DEPTH_MINIMAL 0 /* ring_depth: stage j keeps tau_j + 1 versions, the paper's count
+                                       (Sec. "Fine-grained Pipeline Parallelism", T2: P - j models) */
+
+typedef enum {
+    FERRET_OK = 0,
+    FERRET_EINVAL = 1,   /* bad argument (null, misaligned, out of range) */
+    FERRET_ESTATE = 2,   /* call not valid in the plan's current state */
+    FERRET_ENOMEM = 3,   /* host allocation failed */
+    FERRET_EDEVICE = 4   /* HIP reported an error on launch */
+} ferret_status;
+
+typedef enum {
+    FERRET_F32 = 0,              /* fp32 versions and gradients */
+    FERRET_BF16_MASTER_F32 = 1   /* bf16 versions and gradients, update applied to an fp32 master */
+} ferret_precision;
+
+/* One parameter tensor: element count and the pipeline stage that owns it.  A stage is a
+ * contiguous run of layers (appendix "Notations": |w_j| = sum of |w^_i| over [L_j, L_{j+1})). */
+typedef struct {
+    int64_t numel;     /* > 0 */
+    int32_t stage;     /* 0 .. n_stages-1, non-decreasing over the tensor list */
+    int32_t reserved;  /* must be 0 */
+} ferret_tensor;
+
+/* Optional layout / launch tuning; zero in a field means "library default". */
+typedef struct {
+    int64_t slot_align_elems;  /* slot stride is rounded up to a multiple of this (multiple of 64) */
+    int64_t slot_skew_elems;   /* then this is added (multiple of 8): de-phases the streams that
+                                  read the same element of different slots */
+    int32_t blocks_per_cu;     /* >0: persistent grid of blocks_per_cu * (number of CUs) workgroups;
+                                  <0: one workgroup per chunk; 0: default */
+    int32_t reserved;          /* must be 0 */
+} ferret_tuning;
+
+typedef struct ferret_plan ferret_plan;   /* opaque; host memory; owned by the caller via destroy */
+
+/* ---- planning (host only, no HIP call; Sec. "Model Partitioning and Pipeline Planning" says
+ *      planning runs once, and this is the part of it that the update path consumes) ------------
+ * Flattens the tensors of each stage into one bucket, fixes the layout above, cuts every
+ * stage into chunks of chunk_elems elements (the unit of work of one workgroup; a chunk never
+ * crosses a stage boundary) and records per stage tau_j.
+ *   tensors, n_tensors  host array, model order, stage ids non-decreasing, every stage non-empty
+ *   n_stages            1 .. FERRET_MAX_STAGES
+ *   staleness           host int32[n_stages], 0 <= tau_j (and tau_j < ring_depth if that is > 0);
+ *                       maximum staleness of stage j in a P-stage pipeline is P-1-j
+ *   n_iters             K >= 0, or FERRET_ITERS_FULL
+ *   ring_depth          R >= 1 versions kept per stage, or FERRET_RING_DEPTH_MINIMAL
+ *   chunk_elems         0 = default; otherwise a multiple of 1024 (fp32) / 2048 (bf16)
+ *   tuning              NULL or options
+ *   out_plan            receives the plan; heads start at slot 0 with no valid version
+ */
+ferret_status ferret_plan_buckets(const ferret_tensor *tensors, int32_t n_tensors,
+                                  int32_t n_stages, const int32_t *staleness,
+                                  int32_t n_iters, int32_t ring_depth,
+                                  ferret_precision prec, int64_t chunk_elems,
+                                  ferret_plan **out_plan);
+ferret_status ferret_plan_buckets_tuned(const ferret_tensor *tensors, int32_t n_tensors,
+                                        int32_t n_stages, const int32_t *staleness,
+                                        int32_t n_iters, int32_t ring_depth,
+                                        ferret_precision prec, int64_t chunk_elems,
+                                        const ferret_tuning *tuning, ferret_plan **out_plan);
+void ferret_plan_destroy(ferret_plan *plan);   /* NULL is allowed */
+
+/* ---- plan queries (host; return -1 / 0 on a NULL plan or an index out of range) -------------- */
+int32_t ferret_plan_n_stages(const ferret_plan *plan);
+int32_t ferret_plan_n_tensors(const ferret_plan *plan);
+int32_t ferret_plan_precision(const ferret_plan *plan);
+int32_t ferret_plan_n_iters(const ferret_plan *plan);
+int64_t ferret_plan_chunk_elems(const ferret_plan *plan);
+int64_t ferret_plan_n_chunks(const ferret_plan *plan);
+int64_t ferret_plan_flat_elems(const ferret_plan *plan);      /* elements of a slot-shaped buffer */
+int64_t ferret_plan_ring_elems(const ferret_plan *plan);      /* elements of the whole ring */
+size_t ferret_plan_ring_bytes(const ferret_plan *plan);
+size_t ferret_plan_grad_bytes(const ferret_plan *plan);       /* storage dtype */
+size_t ferret_plan_master_bytes(const ferret_plan *plan);     /* fp32, flat_elems*4 (also grad_out, src) */
+size_t ferret_plan_workspace_bytes(const ferret_plan *plan);  /* per-chunk partial sums for the norms */
+int64_t ferret_plan_total_params(const ferret_plan *plan);    /* sum of tensor numel (no padding) */
+
+int64_t ferret_plan_stage_params(const ferret_plan *plan, int32_t stage);      /* |w_j|, unpadded */
+int64_t ferret_plan_stage_numel(const ferret_plan *plan, int32_t stage);       /* n_j, padded */
+int64_t ferret_plan_stage_flat_offset(const ferret_plan *plan, int32_t stage);
+int64_t ferret_plan_stage_ring_offset(const ferret_plan *plan, int32_t stage);
+int64_t ferret_plan_stage_slot_stride(const ferret_plan *plan, int32_t stage);
+int32_t ferret_plan_stage_ring_depth(const ferret_plan *plan, int32_t stage);
+int32_t ferret_plan_stage_staleness(const ferret_plan *plan, int32_t stage);   /* configured tau_j */
+int64_t ferret_plan_tensor_offset(const ferret_plan *plan, int32_t tensor);    /* inside its stage */
+
+/* ---- ring state (host integers only) --------------------------------------------------------- */
+/* head_j = slot holding the newest version; valid_j = versions held (0 .. ring_depth_j).
+ * get/set let a caller checkpoint the state or adopt a ring it filled itself. */
+ferret_status ferret_plan_get_state(const ferret_plan *plan, int32_t *heads, int32_t *valid);
+ferret_status ferret_plan_set_state(ferret_plan *plan, const int32_t *heads, const int32_t *valid);
+/* What the next step would do for `stage`: effective staleness min(tau_j, valid_j-1) (during
+ * pipeline warm-up fewer than tau_j+1 versions exist), K', the K'+1 slots read oldest first
+ * (returns their count, fills at most cap), and the slot written. */
+int32_t ferret_plan_stage_effective_staleness(const ferret_plan *plan, int32_t stage);
+int32_t ferret_plan_stage_effective_iters(const ferret_plan *plan, int32_t stage);
+int32_t ferret_plan_stage_read_slots(const ferret_plan *plan, int32_t stage, int32_t *slots, int32_t cap);
+int32_t ferret_plan_stage_write_slot(const ferret_plan *plan, int32_t stage);
+/* Algorithmic bytes one step moves in the current state: per parameter, gradient + the K'+1
+ * versions read + the new version (+ master read and write), each once. */
+int64_t ferret_plan_step_bytes(const ferret_plan *plan);
+
+/* ---- version store: push -------------------------------------------------------------------- */
+/* The stage's version store (Alg. 1 inputs theta^{t-1} .. theta^{t+tau-1}; T2 in Sec.
+ * "Fine-grained Pipeline Parallelism" for how many are kept) is a ring: the newest version
+ * lives in slot head_j, the next one goes to (head_j+1) mod R_j and evicts the oldest.
+ *   ring     device, ring_bytes, storage dtype
+ *   master   device fp32 flat buffer or NULL; only with FERRET_BF16_MASTER_F32
+ *   stage    0..n_stages-1, or -1 for every stage
+ *   src      device fp32 flat buffer holding new weights, or NULL.
+ *            src != NULL: for the chosen stage(s) write src (rounded to nearest-even bf16 when
+ *              the ring is bf16) into slot (head+1) mod R, copy it to master if given, then
+ *              advance head and count the version.  Use for initial weights or versions made
+ *              elsewhere.
+ *            src == NULL: commit only -- advance head and count the version that the preceding
+ *              ferret_compensate_step wrote into that slot.  FERRET_ESTATE if no step has been
+ *              issued for the stage since its last commit.
+ * The host state changes when the call returns; the copy itself is ordered on hip_stream.
+ */
+ferret_status ferret_push_version(ferret_plan *plan, void *ring, float *master, int32_t stage,
+                                  const void *src, void *hip_stream);
+
+/* ---- the step -------------------------------------------------------------------------------- */
+/* One fused pass over every stage of the plan: load the stale gradient, the K'_j+1 boundary
+ * versions, iterate A_I K'_j times in registers, apply the update and store the new version
+ * into slot (head_j+1) mod R_j.  Does not advance heads: re-running it recomputes the same
+ * slot from the same inputs, unless that slot is also the oldest version read (ring depth
+ * tau_j+1), in which case the second run sees the first run's output -- commit with
+ * ferret_push_version(.., src = NULL) before the next step.
+ *   ring       device, storage dtype, layout above
+ *   grads      device flat buffer, storage dtype: the stale gradient of every stage
+ *   master     device fp32 flat buffer; required iff FERRET_BF16_MASTER_F32 (updated in place;
+ *              the new version is round-to-nearest-even bf16 of the new master)
+ *   lambda     compensation coefficient (a scalar, may change every call)
+ *   lr         eta
+ *   norms_out  device float[n_stages][3] or NULL: per stage sum g_0^2, sum g_K'^2,
+ *              sum (V[tau]-V[0])^2 (deterministic: per-chunk partials summed in chunk order)
+ *   grad_out   device fp32 flat buffer or NULL: the compensated gradient g_K' (for checks and
+ *              for optimisers that want it)
+ *   workspace  device, workspace_bytes; required iff norms_out != NULL; contents undefined after
+ * FERRET_ESTATE if some stage holds no version yet.
+ */
+ferret_status ferret_compensate_step(const ferret_plan *plan, void *ring, const void *grads,
+                                     float *master, float lambda, float lr, float *norms_out,
+                                     void *grad_out, void *workspace, void *hip_stream);
+
+/* ---- misc ------------------------------------------------------------------------------------ */
+const char *ferret_last_error(void);   /* message of the calling thread's last failed call */
+const char *ferret_version(void);
+
+/* Plain device-to-device copy through the library's own copy kernel (n_bytes multiple of 16,
+ * 16-byte aligned pointers).  Measures the streaming ceiling of the machine with the same
+ * launch shape as the step; not part of the method. */
+ferret_status ferret_copy_bytes(void *dst, const void *src, size_t n_bytes, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FERRET_H */

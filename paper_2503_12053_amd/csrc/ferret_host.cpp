@@ -1,0 +1,404 @@
+// Host side of libferret: the bucket planner, the ring bookkeeping and argument checks of
+// the C ABI declared in include/ferret.h.  No HIP call is made in this file; device work
+// goes through the launchers in ferret_kernels.hip.
+//
+// Paper passages behind the pieces:
+//   stage = contiguous run of layers, |w_j| parameters        appendix "Notations"
+//   tau_j <= P-1, stage j keeps P-j versions                  Sec. "Iterative Gradient Compensation"
+//                                                             (Algorithm Design), T2
+//   what a step computes                                      Alg. 1, lines "iterative approximation"
+//                                                             and "model update"
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "ferret_internal.h"
+
+namespace ferret {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+}
+
+static inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+
+static inline int64_t vec_elems(ferret_precision p) { return p == FERRET_F32 ? 4 : 8; }
+static inline int64_t storage_bytes(ferret_precision p) { return p == FERRET_F32 ? 4 : 2; }
+
+constexpr int64_t kThreads = 256;          // workgroup size of every kernel
+constexpr int64_t kStageAlign = 64;        // stage start alignment in flat buffers / ring
+constexpr int64_t kDefaultSlotAlign = 64;
+
+static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Fill the per-stage device descriptors for the state the plan is in right now.
+static void fill_step_descs(const ferret_plan &p, StageDesc *out) {
+    for (size_t j = 0; j < p.stages.size(); ++j) {
+        const Stage &s = p.stages[j];
+        StageDesc &d = out[j];
+        d.ring_base = (uint64_t)s.ring_base;
+        d.slot_stride = (uint64_t)s.slot_stride;
+        d.flat_off = (uint64_t)s.flat_off;
+        d.n_elems = (uint64_t)s.n_elems;
+        d.chunk_begin = (uint32_t)s.chunk_begin;
+        d.ring_depth = (uint16_t)s.ring_depth;
+        d.head = (uint16_t)s.head;
+        int32_t tau = effective_tau(s);
+        d.tau = (uint16_t)tau;
+        d.kp = (uint16_t)effective_iters(p.n_iters, tau);
+    }
+}
+
+}  // namespace ferret
+
+using namespace ferret;
+
+extern "C" {
+
+const char *ferret_last_error(void) { return g_err; }
+const char *ferret_version(void) { return "libferret 0.1 (gfx950)"; }
+
+ferret_status ferret_plan_buckets(const ferret_tensor *tensors, int32_t n_tensors, int32_t n_stages,
+                                  const int32_t *staleness, int32_t n_iters, int32_t ring_depth,
+                                  ferret_precision prec, int64_t chunk_elems, ferret_plan **out_plan) {
+    return ferret_plan_buckets_tuned(tensors, n_tensors, n_stages, staleness, n_iters, ring_depth,
+                                     prec, chunk_elems, nullptr, out_plan);
+}
+
+ferret_status ferret_plan_buckets_tuned(const ferret_tensor *tensors, int32_t n_tensors,
+                                        int32_t n_stages, const int32_t *staleness, int32_t n_iters,
+                                        int32_t ring_depth, ferret_precision prec, int64_t chunk_elems,
+                                        const ferret_tuning *tuning, ferret_plan **out_plan) {
+    if (out_plan) *out_plan = nullptr;
+    if (!tensors || !staleness || !out_plan) { set_error("plan: null argument"); return FERRET_EINVAL; }
+    if (n_tensors < 1) { set_error("plan: n_tensors = %d, need >= 1", n_tensors); return FERRET_EINVAL; }
+    if (n_stages < 1 || n_stages > FERRET_MAX_STAGES) {
+        set_error("plan: n_stages = %d, need 1..%d", n_stages, FERRET_MAX_STAGES); return FERRET_EINVAL;
+    }
+    if (n_iters < 0 && n_iters != FERRET_ITERS_FULL) {
+        set_error("plan: n_iters = %d, need >= 0 or FERRET_ITERS_FULL", n_iters); return FERRET_EINVAL;
+    }
+    if (ring_depth < 0 || ring_depth > FERRET_MAX_RING_DEPTH) {
+        set_error("plan: ring_depth = %d, need 0..%d", ring_depth, FERRET_MAX_RING_DEPTH); return FERRET_EINVAL;
+    }
+    if (prec != FERRET_F32 && prec != FERRET_BF16_MASTER_F32) {
+        set_error("plan: unknown precision %d", (int)prec); return FERRET_EINVAL;
+    }
+    const int64_t vec = vec_elems(prec);
+    const int64_t chunk_unit = kThreads * vec;                 // one vector per thread
+    if (chunk_elems == 0) chunk_elems = chunk_unit * 8;
+    if (chunk_elems < 0 || chunk_elems % chunk_unit != 0 || chunk_elems > (int64_t(1) << 30)) {
+        set_error("plan: chunk_elems = %lld, need a positive multiple of %lld", (long long)chunk_elems,
+                  (long long)chunk_unit);
+        return FERRET_EINVAL;
+    }
+    int64_t slot_align = kDefaultSlotAlign, slot_skew = 0;
+    int32_t blocks_per_cu = 0;
+    if (tuning) {
+        if (tuning->reserved != 0) { set_error("plan: tuning.reserved must be 0"); return FERRET_EINVAL; }
+        if (tuning->slot_align_elems) slot_align = tuning->slot_align_elems;
+        slot_skew = tuning->slot_skew_elems;
+        blocks_per_cu = tuning->blocks_per_cu;
+        if (slot_align < 0 || slot_align % kStageAlign != 0) {
+            set_error("plan: slot_align_elems = %lld, need a multiple of %lld", (long long)slot_align,
+                      (long long)kStageAlign);
+            return FERRET_EINVAL;
+        }
+        if (slot_skew < 0 || slot_skew % FERRET_ALIGN_ELEMS != 0) {
+            set_error("plan: slot_skew_elems = %lld, need a non-negative multiple of %d",
+                      (long long)slot_skew, FERRET_ALIGN_ELEMS);
+            return FERRET_EINVAL;
+        }
+        if (blocks_per_cu > 64) { set_error("plan: blocks_per_cu = %d, need <= 64", blocks_per_cu); return FERRET_EINVAL; }
+    }
+    for (int32_t j = 0; j < n_stages; ++j) {
+        if (staleness[j] < 0) { set_error("plan: staleness[%d] = %d < 0", j, staleness[j]); return FERRET_EINVAL; }
+        if (ring_depth > 0 && staleness[j] >= ring_depth) {
+            set_error("plan: staleness[%d] = %d needs %d stored versions but ring_depth = %d", j,
+                      staleness[j], staleness[j] + 1, ring_depth);
+            return FERRET_EINVAL;
+        }
+        if (staleness[j] >= FERRET_MAX_RING_DEPTH) {
+            set_error("plan: staleness[%d] = %d too large", j, staleness[j]); return FERRET_EINVAL;
+        }
+    }
+
+    ferret_plan *p = new (std::nothrow) ferret_plan();
+    if (!p) { set_error("plan: out of host memory"); return FERRET_ENOMEM; }
+    try {
+        p->stages.resize(n_stages);
+        p->tensor_offset.resize(n_tensors);
+        p->tensor_stage.resize(n_tensors);
+    } catch (const std::bad_alloc &) {
+        delete p; set_error("plan: out of host memory"); return FERRET_ENOMEM;
+    }
+    p->prec = prec;
+    p->n_iters = n_iters;
+    p->chunk_elems = chunk_elems;
+    p->blocks_per_cu = blocks_per_cu;
+
+    // tensors -> stage buckets
+    int32_t prev_stage = 0;
+    for (int32_t i = 0; i < n_tensors; ++i) {
+        const ferret_tensor &t = tensors[i];
+        if (t.numel <= 0 || t.reserved != 0 || t.stage < 0 || t.stage >= n_stages) {
+            set_error("plan: tensor %d: numel = %lld, stage = %d, reserved = %d", i, (long long)t.numel,
+                      t.stage, t.reserved);
+            delete p; return FERRET_EINVAL;
+        }
+        if (t.stage < prev_stage || t.stage > prev_stage + 1 || (i == 0 && t.stage != 0)) {
+            set_error("plan: tensor %d is in stage %d after stage %d: stage ids must be non-decreasing "
+                      "and every stage non-empty", i, t.stage, prev_stage);
+            delete p; return FERRET_EINVAL;
+        }
+        prev_stage = t.stage;
+        Stage &s = p->stages[t.stage];
+        p->tensor_stage[i] = t.stage;
+        p->tensor_offset[i] = s.n_elems;
+        s.params += t.numel;
+        s.n_elems = round_up(s.n_elems + t.numel, FERRET_ALIGN_ELEMS);
+        p->total_params += t.numel;
+    }
+    if (prev_stage != n_stages - 1) {
+        set_error("plan: stages %d..%d own no tensor", prev_stage + 1, n_stages - 1);
+        delete p; return FERRET_EINVAL;
+    }
+
+    // layout + chunks
+    int64_t flat = 0, ring = 0, chunks = 0;
+    for (int32_t j = 0; j < n_stages; ++j) {
+        Stage &s = p->stages[j];
+        s.tau = staleness[j];
+        s.ring_depth = ring_depth > 0 ? ring_depth : staleness[j] + 1;
+        s.flat_off = flat;
+        flat += round_up(s.n_elems, kStageAlign);
+        s.slot_stride = round_up(s.n_elems, slot_align) + slot_skew;
+        s.ring_base = ring;
+        ring += round_up(s.slot_stride * s.ring_depth, kStageAlign);
+        s.chunk_begin = chunks;
+        s.n_chunks = (s.n_elems + chunk_elems - 1) / chunk_elems;
+        chunks += s.n_chunks;
+    }
+    if (chunks > 0x7fffffffLL) { set_error("plan: %lld chunks, too many; raise chunk_elems", (long long)chunks); delete p; return FERRET_EINVAL; }
+    p->flat_elems = flat;
+    p->ring_elems = ring;
+    p->n_chunks = chunks;
+    *out_plan = p;
+    return FERRET_OK;
+}
+
+void ferret_plan_destroy(ferret_plan *plan) { delete plan; }
+
+// ---- queries ----------------------------------------------------------------------------------
+#define STAGE_OR(ret) \
+    if (!plan || stage < 0 || stage >= (int32_t)plan->stages.size()) return ret; \
+    const Stage &s = plan->stages[stage]
+
+int32_t ferret_plan_n_stages(const ferret_plan *plan) { return plan ? (int32_t)plan->stages.size() : -1; }
+int32_t ferret_plan_n_tensors(const ferret_plan *plan) { return plan ? (int32_t)plan->tensor_offset.size() : -1; }
+int32_t ferret_plan_precision(const ferret_plan *plan) { return plan ? (int32_t)plan->prec : -1; }
+int32_t ferret_plan_n_iters(const ferret_plan *plan) { return plan ? plan->n_iters : 0; }
+int64_t ferret_plan_chunk_elems(const ferret_plan *plan) { return plan ? plan->chunk_elems : -1; }
+int64_t ferret_plan_n_chunks(const ferret_plan *plan) { return plan ? plan->n_chunks : -1; }
+int64_t ferret_plan_flat_elems(const ferret_plan *plan) { return plan ? plan->flat_elems : -1; }
+int64_t ferret_plan_ring_elems(const ferret_plan *plan) { return plan ? plan->ring_elems : -1; }
+size_t ferret_plan_ring_bytes(const ferret_plan *plan) { return plan ? (size_t)(plan->ring_elems * storage_bytes(plan->prec)) : 0; }
+size_t ferret_plan_grad_bytes(const ferret_plan *plan) { return plan ? (size_t)(plan->flat_elems * storage_bytes(plan->prec)) : 0; }
+size_t ferret_plan_master_bytes(const ferret_plan *plan) { return plan ? (size_t)(plan->flat_elems * 4) : 0; }
+size_t ferret_plan_workspace_bytes(const ferret_plan *plan) {
+    return plan ? (size_t)round_up(plan->n_chunks * 3 * (int64_t)sizeof(float), 256) : 0;
+}
+int64_t ferret_plan_total_params(const ferret_plan *plan) { return plan ? plan->total_params : -1; }
+
+int64_t ferret_plan_stage_params(const ferret_plan *plan, int32_t stage) { STAGE_OR(-1); return s.params; }
+int64_t ferret_plan_stage_numel(const ferret_plan *plan, int32_t stage) { STAGE_OR(-1); return s.n_elems; }
+int64_t ferret_plan_stage_flat_offset(const ferret_plan *plan, int32_t stage) { STAGE_OR(-1); return s.flat_off; }
+int64_t ferret_plan_stage_ring_offset(const ferret_plan *plan, int32_t stage) { STAGE_OR(-1); return s.ring_base; }
+int64_t ferret_plan_stage_slot_stride(const ferret_plan *plan, int32_t stage) { STAGE_OR(-1); return s.slot_stride; }
+int32_t ferret_plan_stage_ring_depth(const ferret_plan *plan, int32_t stage) { STAGE_OR(-1); return s.ring_depth; }
+int32_t ferret_plan_stage_staleness(const ferret_plan *plan, int32_t stage) { STAGE_OR(-1); return s.tau; }
+int64_t ferret_plan_tensor_offset(const ferret_plan *plan, int32_t tensor) {
+    if (!plan || tensor < 0 || tensor >= (int32_t)plan->tensor_offset.size()) return -1;
+    return plan->tensor_offset[tensor];
+}
+
+// ---- ring state -------------------------------------------------------------------------------
+ferret_status ferret_plan_get_state(const ferret_plan *plan, int32_t *heads, int32_t *valid) {
+    if (!plan || !heads || !valid) { set_error("get_state: null argument"); return FERRET_EINVAL; }
+    for (size_t j = 0; j < plan->stages.size(); ++j) {
+        heads[j] = plan->stages[j].head;
+        valid[j] = plan->stages[j].valid;
+    }
+    return FERRET_OK;
+}
+
+ferret_status ferret_plan_set_state(ferret_plan *plan, const int32_t *heads, const int32_t *valid) {
+    if (!plan || !heads || !valid) { set_error("set_state: null argument"); return FERRET_EINVAL; }
+    for (size_t j = 0; j < plan->stages.size(); ++j) {
+        const Stage &s = plan->stages[j];
+        if (heads[j] < 0 || heads[j] >= s.ring_depth || valid[j] < 0 || valid[j] > s.ring_depth) {
+            set_error("set_state: stage %zu: head = %d, valid = %d, ring depth = %d", j, heads[j], valid[j],
+                      s.ring_depth);
+            return FERRET_EINVAL;
+        }
+    }
+    for (size_t j = 0; j < plan->stages.size(); ++j) {
+        plan->stages[j].head = heads[j];
+        plan->stages[j].valid = valid[j];
+        plan->stages[j].step_pending = false;
+    }
+    return FERRET_OK;
+}
+
+int32_t ferret_plan_stage_effective_staleness(const ferret_plan *plan, int32_t stage) {
+    STAGE_OR(-1);
+    return effective_tau(s);
+}
+int32_t ferret_plan_stage_effective_iters(const ferret_plan *plan, int32_t stage) {
+    STAGE_OR(-1);
+    return effective_iters(plan->n_iters, effective_tau(s));
+}
+int32_t ferret_plan_stage_read_slots(const ferret_plan *plan, int32_t stage, int32_t *slots, int32_t cap) {
+    STAGE_OR(-1);
+    if (s.valid < 1) return 0;
+    const int32_t tau = effective_tau(s), kp = effective_iters(plan->n_iters, tau), R = s.ring_depth;
+    const int32_t n = kp + 1;
+    for (int32_t i = 0; i < n && slots && i < cap; ++i) {
+        int32_t age_from_oldest = kp == 0 ? tau : (int32_t)(((int64_t)i * tau) / kp);   // s_i
+        slots[i] = ((s.head - (tau - age_from_oldest)) % R + R) % R;
+    }
+    return n;
+}
+int32_t ferret_plan_stage_write_slot(const ferret_plan *plan, int32_t stage) {
+    STAGE_OR(-1);
+    return s.valid == 0 ? s.head : (s.head + 1) % s.ring_depth;
+}
+
+int64_t ferret_plan_step_bytes(const ferret_plan *plan) {
+    if (!plan) return -1;
+    int64_t bytes = 0;
+    const int64_t sb = storage_bytes(plan->prec);
+    for (const Stage &s : plan->stages) {
+        const int32_t kp = effective_iters(plan->n_iters, effective_tau(s));
+        int64_t per = sb /*grad*/ + sb * (kp + 1) /*versions*/ + sb /*new version*/;
+        if (plan->prec == FERRET_BF16_MASTER_F32) per += 8;   // master read + write
+        bytes += per * s.params;
+    }
+    return bytes;
+}
+
+// ---- push --------------------------------------------------------------------------------------
+static void advance(Stage &s) {
+    if (s.valid > 0) s.head = (s.head + 1) % s.ring_depth;   // the very first version lands in slot head
+    if (s.valid < s.ring_depth) ++s.valid;
+    s.step_pending = false;
+}
+
+ferret_status ferret_push_version(ferret_plan *plan, void *ring, float *master, int32_t stage,
+                                  const void *src, void *hip_stream) {
+    if (!plan) { set_error("push_version: null plan"); return FERRET_EINVAL; }
+    const int32_t P = (int32_t)plan->stages.size();
+    if (stage < -1 || stage >= P) { set_error("push_version: stage = %d, need -1..%d", stage, P - 1); return FERRET_EINVAL; }
+    const int32_t j0 = stage < 0 ? 0 : stage, j1 = stage < 0 ? P : stage + 1;
+
+    if (!src) {   // commit only
+        for (int32_t j = j0; j < j1; ++j)
+            if (!plan->stages[j].step_pending) {
+                set_error("push_version: commit of stage %d without a step since its last commit", j);
+                return FERRET_ESTATE;
+            }
+        for (int32_t j = j0; j < j1; ++j) advance(plan->stages[j]);
+        return FERRET_OK;
+    }
+
+    if (!ring) { set_error("push_version: null ring"); return FERRET_EINVAL; }
+    if (!aligned16(ring) || !aligned16(src) || !aligned16(master)) {
+        set_error("push_version: device pointers must be 16-byte aligned"); return FERRET_EINVAL;
+    }
+    if (master && plan->prec != FERRET_BF16_MASTER_F32) {
+        set_error("push_version: master given but the plan is fp32"); return FERRET_EINVAL;
+    }
+    PushArgs a;
+    memset(&a, 0, sizeof a);
+    a.ring = ring;
+    a.master = master;
+    a.src = static_cast<const float *>(src);
+    a.chunk_elems = (uint32_t)plan->chunk_elems;
+    uint32_t chunks = 0, n = 0;
+    for (int32_t j = j0; j < j1; ++j, ++n) {
+        const Stage &s = plan->stages[j];
+        StageDesc &d = a.stage[n];
+        d.ring_base = (uint64_t)s.ring_base;
+        d.slot_stride = (uint64_t)s.slot_stride;
+        d.flat_off = (uint64_t)s.flat_off;
+        d.n_elems = (uint64_t)s.n_elems;
+        d.chunk_begin = chunks;
+        d.ring_depth = (uint16_t)s.ring_depth;
+        d.head = (uint16_t)(s.valid == 0 ? s.head : (s.head + 1) % s.ring_depth);   // slot written
+        chunks += (uint32_t)s.n_chunks;
+    }
+    a.n_stages = n;
+    a.n_chunks = chunks;
+    int err = launch_push(*plan, a, hip_stream);
+    if (err) { set_error("push_version: launch failed: %s", device_error_string(err)); return FERRET_EDEVICE; }
+    for (int32_t j = j0; j < j1; ++j) advance(plan->stages[j]);
+    return FERRET_OK;
+}
+
+// ---- step --------------------------------------------------------------------------------------
+ferret_status ferret_compensate_step(const ferret_plan *plan, void *ring, const void *grads, float *master,
+                                     float lambda, float lr, float *norms_out, void *grad_out,
+                                     void *workspace, void *hip_stream) {
+    if (!plan || !ring || !grads) { set_error("compensate_step: null plan, ring or grads"); return FERRET_EINVAL; }
+    const bool mixed = plan->prec == FERRET_BF16_MASTER_F32;
+    if (mixed && !master) { set_error("compensate_step: bf16 plan needs the fp32 master"); return FERRET_EINVAL; }
+    if (!mixed && master) { set_error("compensate_step: master given but the plan is fp32"); return FERRET_EINVAL; }
+    if (norms_out && !workspace) { set_error("compensate_step: norms_out needs workspace"); return FERRET_EINVAL; }
+    if (!aligned16(ring) || !aligned16(grads) || !aligned16(master) || !aligned16(grad_out) ||
+        !aligned16(workspace) || (reinterpret_cast<uintptr_t>(norms_out) & 3u)) {
+        set_error("compensate_step: device pointers must be 16-byte aligned"); return FERRET_EINVAL;
+    }
+    for (size_t j = 0; j < plan->stages.size(); ++j)
+        if (plan->stages[j].valid < 1) {
+            set_error("compensate_step: stage %zu holds no weight version yet (push one first)", j);
+            return FERRET_ESTATE;
+        }
+
+    StepArgs a;
+    a.ring = ring;
+    a.grads = grads;
+    a.master = master;
+    a.grad_out = static_cast<float *>(grad_out);
+    a.partials = norms_out ? static_cast<float *>(workspace) : nullptr;
+    a.lambda = lambda;
+    a.lr = lr;
+    a.n_stages = (uint32_t)plan->stages.size();
+    a.n_chunks = (uint32_t)plan->n_chunks;
+    a.chunk_elems = (uint32_t)plan->chunk_elems;
+    a.pad_ = 0;
+    fill_step_descs(*plan, a.stage);
+    int err = launch_step(*plan, a, norms_out, hip_stream);
+    if (err) { set_error("compensate_step: launch failed: %s", device_error_string(err)); return FERRET_EDEVICE; }
+    // bookkeeping only: remembers that slot head+1 now holds an uncommitted version
+    for (const Stage &s : plan->stages) s.step_pending = true;
+    return FERRET_OK;
+}
+
+ferret_status ferret_copy_bytes(void *dst, const void *src, size_t n_bytes, void *hip_stream) {
+    if (!dst || !src || !aligned16(dst) || !aligned16(src) || (n_bytes & 15u)) {
+        set_error("copy_bytes: need non-null 16-byte aligned pointers and a multiple of 16 bytes");
+        return FERRET_EINVAL;
+    }
+    if (n_bytes == 0) return FERRET_OK;
+    int err = launch_copy(dst, src, n_bytes, hip_stream);
+    if (err) { set_error("copy_bytes: launch failed: %s", device_error_string(err)); return FERRET_EDEVICE; }
+    return FERRET_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,109 @@
+// Internal declarations shared by the host planner (ferret_host.cpp) and the kernel
+// launchers (ferret_kernels.hip).  Not installed; the public interface is include/ferret.h.
+#pragma once
+
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "ferret.h"
+
+namespace ferret {
+
+// ---- what travels to the device as a kernel argument -------------------------------------
+// One entry per pipeline stage.  48 bytes; FERRET_MAX_STAGES of them stay under the 4 KiB
+// kernel-argument limit.  Every workgroup copies the live entries into LDS once and looks
+// chunks up there.
+struct StageDesc {
+    uint64_t ring_base;    // element offset of the stage's arena in the ring
+    uint64_t slot_stride;  // elements between consecutive slots
+    uint64_t flat_off;     // element offset of the stage in slot-shaped buffers
+    uint64_t n_elems;      // padded elements in the stage (multiple of FERRET_ALIGN_ELEMS)
+    uint32_t chunk_begin;  // id of the stage's first chunk
+    uint16_t ring_depth;   // R_j
+    uint16_t head;         // slot of the newest version, V[tau]
+    uint16_t tau;          // effective staleness this step
+    uint16_t kp;           // K' this step (0 = no compensation)
+};
+static_assert(sizeof(StageDesc) == 48, "StageDesc layout");
+
+struct StepArgs {
+    void *ring;
+    const void *grads;
+    float *master;
+    float *grad_out;   // nullable
+    float *partials;   // float[n_chunks][3], nullable
+    float lambda;
+    float lr;
+    uint32_t n_stages;
+    uint32_t n_chunks;
+    uint32_t chunk_elems;
+    uint32_t pad_;
+    StageDesc stage[FERRET_MAX_STAGES];
+};
+static_assert(sizeof(StepArgs) <= 3400, "StepArgs must fit the kernel-argument segment");
+
+struct PushArgs {
+    void *ring;
+    float *master;     // nullable
+    const float *src;
+    uint32_t n_stages; // entries used in stage[]
+    uint32_t n_chunks;
+    uint32_t chunk_elems;
+    uint32_t pad_;
+    StageDesc stage[FERRET_MAX_STAGES];   // head = slot to WRITE; chunk_begin re-based to the pushed set
+};
+
+// ---- host-side plan ------------------------------------------------------------------------
+struct Stage {
+    int64_t params = 0;       // |w_j|
+    int64_t n_elems = 0;      // padded
+    int64_t flat_off = 0;
+    int64_t ring_base = 0;
+    int64_t slot_stride = 0;
+    int64_t chunk_begin = 0;
+    int64_t n_chunks = 0;
+    int32_t ring_depth = 0;
+    int32_t tau = 0;          // configured staleness
+    int32_t head = 0;
+    int32_t valid = 0;
+    mutable bool step_pending = false;  // a step wrote slot head+1 and it has not been committed
+                                        // (bookkeeping that a step on a const plan may set)
+};
+
+}  // namespace ferret
+
+struct ferret_plan {
+    std::vector<ferret::Stage> stages;
+    std::vector<int64_t> tensor_offset;   // inside the stage
+    std::vector<int32_t> tensor_stage;
+    ferret_precision prec = FERRET_F32;
+    int32_t n_iters = 0;
+    int64_t chunk_elems = 0;
+    int64_t n_chunks = 0;
+    int64_t flat_elems = 0;
+    int64_t ring_elems = 0;
+    int64_t total_params = 0;
+    int32_t blocks_per_cu = 0;
+};
+
+namespace ferret {
+
+void set_error(const char *fmt, ...) __attribute__((format(printf, 1, 2)));
+
+// effective staleness / iteration count / segment boundary for the plan's current state
+inline int32_t effective_tau(const Stage &s) {
+    int32_t have = s.valid - 1;
+    return have < s.tau ? (have < 0 ? 0 : have) : s.tau;
+}
+inline int32_t effective_iters(int32_t n_iters, int32_t tau) {
+    return n_iters < 0 ? tau : (n_iters < tau ? n_iters : tau);
+}
+
+// launchers implemented in ferret_kernels.hip; return hipError_t as int (0 = success)
+int launch_step(const ferret_plan &plan, const StepArgs &args, float *norms_out, void *stream);
+int launch_push(const ferret_plan &plan, const PushArgs &args, void *stream);
+int launch_copy(void *dst, const void *src, size_t n_bytes, void *stream);
+const char *device_error_string(int err);
+
+}  // namespace ferret

@@ -1,0 +1,131 @@
+"""Helpers shared by the GPU parity tests: run one step through the C ABI on the device and
+the same step through the CPU oracle, and compare element by element.
+
+Tolerances (written here once, used by every parity test):
+  fp32 outputs (new version, g_K', master):  |gpu - ref| <= 1e-5 * |ref| + 1e-5 * rms(ref)
+      The device computes in fp32 with fused multiply-adds (a few 1e-7 relative per
+      iteration), the oracle in fp64 rounded once; the rms term only matters for elements
+      that cancel to (almost) zero, where a relative bound has no meaning.
+  bf16 outputs (new version):                at most 1 bf16 ulp from the oracle's bits
+      (both sides round the fp32 master to nearest-even; they can differ only when the two
+      fp32 masters straddle a rounding boundary)
+  norms:                                     relative 1e-5 against the oracle's fp64 sums
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from oracle import ferret_oracle as O
+from paper_2503_12053_amd import binding as B
+from paper_2503_12053_amd import workloads as W
+
+RTOL = 1e-5
+
+
+def assert_close_f32(got, ref, what):
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert got.shape == ref.shape, what
+    both_nan = np.isnan(got) & np.isnan(ref)
+    same_inf = np.isinf(ref) & (got == ref)
+    finite = np.isfinite(ref) & np.isfinite(got)
+    assert np.all(both_nan | same_inf | finite), f"{what}: non-finite mismatch"
+    if not finite.any():
+        return 0.0
+    rms = float(np.sqrt(np.mean(ref[finite] ** 2)))
+    err = np.abs(got[finite] - ref[finite])
+    bound = RTOL * np.abs(ref[finite]) + RTOL * rms
+    worst = int(np.argmax(err - bound))
+    assert np.all(err <= bound), (f"{what}: {int((err > bound).sum())} of {err.size} elements out of tolerance; "
+                                  f"worst got {got[finite][worst]!r} ref {ref[finite][worst]!r}")
+    return float((err / np.maximum(np.abs(ref[finite]), rms)).max())
+
+
+def bf16_ulp_distance(a_bits, b_bits):
+    """Distance in representable bf16 steps between two arrays of bit patterns."""
+    def key(x):
+        x = x.astype(np.int32)
+        return np.where(x & 0x8000, 0x8000 - (x & 0x7FFF) - 1 + 0, 0x8000 + (x & 0x7FFF))
+    return np.abs(key(np.asarray(a_bits, dtype=np.uint16)) - key(np.asarray(b_bits, dtype=np.uint16)))
+
+
+def assert_bf16_within_one_ulp(got_bits, ref_bits, what):
+    got_bits = np.asarray(got_bits, dtype=np.uint16)
+    ref_bits = np.asarray(ref_bits, dtype=np.uint16)
+    def isnan(b):
+        return ((b & 0x7F80) == 0x7F80) & ((b & 0x007F) != 0)
+    nan_g, nan_r = isnan(got_bits), isnan(ref_bits)
+    assert np.array_equal(nan_g, nan_r), f"{what}: NaN pattern differs"
+    d = bf16_ulp_distance(got_bits[~nan_r], ref_bits[~nan_r])
+    # +0 and -0 are one step apart in the key above; both are zero
+    assert d.size == 0 or d.max() <= 1, f"{what}: {int((d > 1).sum())} elements differ by more than 1 bf16 ulp (max {d.max()})"
+    return float((d != 0).mean()) if d.size else 0.0
+
+
+def bits_of(t: torch.Tensor) -> np.ndarray:
+    return t.contiguous().view(torch.int16).numpy().view(np.uint16)
+
+
+def tensors_of(w: W.Workload):
+    return [(n, s) for _, n, s in w.tensors]
+
+
+def load_workload(w: W.Workload, amplified=False, chunk_elems=0, tuning=None, heads=None, n_iters=None,
+                  ring_depth=None, device="cuda"):
+    """Plan + device state with every ring slot valid, filled from the seeded generator.
+    Returns (plan, state, host_data) where host_data[j] is the StageData kept for the oracle."""
+    plan = B.plan_for_workload(w, chunk_elems=chunk_elems, tuning=tuning, n_iters=n_iters,
+                               ring_depth=ring_depth)
+    st = B.DeviceState(plan, tensors_of(w), device=device)
+    host, hd, valid = [], [], []
+    for j in range(w.n_stages):
+        R = plan.stage_ring_depth(j)
+        data = W.generate_stage(w, j, amplified, n_versions=R)
+        h = st.load_versions(j, data.versions, None if heads is None else heads[j] % R)
+        st.set_flat(st.grads, j, data.grads)
+        if data.master is not None:
+            st.set_flat(st.master, j, data.master)
+        hd.append(h)
+        valid.append(R)
+        host.append(data)
+    plan.set_state(hd, valid)
+    return plan, st, host
+
+
+def oracle_stage(w: W.Workload, data: W.StageData, tau: int, K: int, lam=None, lr=None, n_threads=1):
+    """Oracle result of one stage given its newest tau+1 versions."""
+    lam = w.lam if lam is None else lam
+    lr = w.lr if lr is None else lr
+    window = data.versions[len(data.versions) - 1 - tau:]
+    if w.precision == "f32":
+        new, g_out, norms = O.compensate_stage_f32(window, data.grads, K, np.float32(lam), np.float32(lr),
+                                                   n_threads=n_threads)
+        return dict(new=new, g=g_out, norms=norms)
+    new, m_new, g_out, norms = O.compensate_stage_bf16(window, data.grads, data.master, K, np.float32(lam),
+                                                       np.float32(lr), n_threads=n_threads)
+    return dict(new=new, master=m_new, g=g_out, norms=norms)
+
+
+def check_step_against_oracle(w, plan, st, host, K=None, lam=None, lr=None, n_threads=1, label=""):
+    """After st.step(...) + synchronize: compare every stage with the oracle.  Returns stats."""
+    K = w.n_iters if K is None else K
+    norms = st.norms.cpu().numpy().astype(np.float64)
+    stats = {}
+    for j in range(w.n_stages):
+        tau = plan.stage_effective_staleness(j)
+        ref = oracle_stage(w, host[j], tau, K, lam, lr, n_threads)
+        slot = plan.stage_write_slot(j)
+        tag = f"{label}{w.name} stage {j}"
+        got_g = st.get_flat(st.grad_out, j).numpy()
+        stats[f"g{j}"] = assert_close_f32(got_g, ref["g"], tag + " g_K'")
+        if w.precision == "f32":
+            got_new = st.get_version(j, slot).numpy()
+            stats[f"w{j}"] = assert_close_f32(got_new, ref["new"], tag + " new version")
+        else:
+            got_new = bits_of(st.get_version(j, slot))
+            stats[f"w{j}"] = assert_bf16_within_one_ulp(got_new, ref["new"], tag + " new version (bf16)")
+            got_m = st.get_flat(st.master, j).numpy()
+            stats[f"m{j}"] = assert_close_f32(got_m, ref["master"], tag + " master")
+        np.testing.assert_allclose(norms[j], ref["norms"], rtol=RTOL, atol=1e-30, err_msg=tag + " norms")
+    return stats

@@ -1,0 +1,289 @@
+"""GPU parity: the HIP path (called through the C ABI) against the CPU oracle, element by
+element, on identical seeded inputs.  Tolerances are defined in tests/parity_util.py.
+
+Run on an MI355X with:  python -u -m pytest tests -m gpu -x -v --timeout 300 --timeout-method thread
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ferret_oracle as O
+from paper_2503_12053_amd import binding as B
+from paper_2503_12053_amd import workloads as W
+
+import parity_util as PU
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _gpu():
+    if not torch.cuda.is_available():
+        pytest.fail("these tests need a GPU (run with -m 'not gpu' elsewhere)")
+    B.load()          # raises if libferret.so is not built: there is no fallback
+    print("device:", torch.cuda.get_device_name(0), flush=True)
+
+
+def _run(w, amplified=False, label="", **kw):
+    print(f"[case] {label or w.name} amplified={amplified} {kw}", flush=True)
+    plan, st, host = PU.load_workload(w, amplified=amplified, **kw)
+    st.step(w.lam, w.lr)
+    torch.cuda.synchronize()
+    stats = PU.check_step_against_oracle(w, plan, st, host, K=kw.get("n_iters"), n_threads=4, label=label)
+    return plan, st, host, stats
+
+
+# ---- the benchmark configurations -------------------------------------------------------------
+@pytest.mark.parametrize("idx", [1, 2, 3])
+@pytest.mark.parametrize("amplified", [False, True])
+def test_benchmark_configs_small(idx, amplified):
+    _run(W.make_workload(idx), amplified)
+
+
+@pytest.mark.parametrize("amplified", [False, True])
+def test_benchmark_config_4_full_size(amplified):
+    """ViT-B-sized: the launch configuration the benchmark times (default chunking and grid)."""
+    _run(W.make_workload(4), amplified)
+
+
+@pytest.mark.timeout(900)
+def test_benchmark_config_5_full_size():
+    """350 M parameters, bf16 + fp32 master, heavy-tailed gradients; whole arrays are compared."""
+    w = W.make_workload(5)
+    plan, st, host, stats = _run(w, False)
+    # the heavy tail makes the compensation visible in the master (|g| ~ 1 entries)
+    assert plan.step_bytes == sum((14 + 2 * min(4, t)) * n for t, n in zip(w.staleness, w.stage_numel()))
+
+
+def test_benchmark_config_5_shape_amplified_two_stages():
+    """Same dtype path with the compensation term at a few per cent, on a 2-stage cut of the shape."""
+    w = W.custom_workload("mixed_amplified", [[21_875_000 // 8], [21_875_000 // 8]], [15, 3], 16, 4, lam=0.3,
+                          lr=0.005, precision="bf16", seed=41, heavy_tail=(0.01, 100.0))
+    _run(w, True)
+
+
+# ---- ragged shapes, many chunks, tiny stages ---------------------------------------------------
+RAGGED = [
+    ("one_element", [[1]], [1], 2, -1),
+    ("odd_tensors", [[1, 3, 1001, 64, 4097], [7], [5000, 13]], [2, 1, 0], 3, -1),
+    ("tail_of_8", [[1024 * 3 + 8]], [1], 2, 1),
+    ("multi_chunk_ragged", [[10_000, 33, 70_001], [2048], [123_457]], [3, 2, 1], 4, 2),
+]
+
+
+@pytest.mark.parametrize("name,sizes,tau,R,K", RAGGED)
+@pytest.mark.parametrize("precision", ["f32", "bf16"])
+@pytest.mark.parametrize("chunk_units", [1, 0])
+def test_ragged_shapes(name, sizes, tau, R, K, precision, chunk_units):
+    unit = 1024 if precision == "f32" else 2048
+    w = W.custom_workload(name, sizes, tau, R, K, precision=precision, seed=7)
+    _run(w, True, chunk_elems=chunk_units * unit)
+
+
+# ---- iteration counts: none, single step, segments, one per version step, streamed ---------------
+@pytest.mark.parametrize("K", [0, 1, 2, 3, 4, 5, 6, -1])
+@pytest.mark.parametrize("precision", ["f32", "bf16"])
+def test_iteration_counts(K, precision):
+    w = W.custom_workload("iters", [[40_000, 24], [9_000], [31_000]], [7, 4, 0], 8, K, precision=precision, seed=11)
+    plan, st, host, _ = _run(w, True, n_iters=K)
+    for j, tau in enumerate(w.staleness):
+        assert plan.stage_effective_iters(j) == O.effective_iters(K, tau)
+
+
+def test_deep_staleness_streamed_path():
+    w = W.custom_workload("deep", [[70_000], [50_000]], [15, 11], 16, -1, seed=12, lam=0.3)
+    _run(w, True)
+
+
+# ---- ring positions and the in-place case --------------------------------------------------------
+@pytest.mark.parametrize("head_shift", [0, 1, 2, 3])
+def test_every_head_position(head_shift):
+    w = W.custom_workload("heads", [[30_000], [30_000], [30_000], [30_000]], [3, 2, 1, 0], 4, 2, seed=13)
+    _run(w, True, heads=[head_shift, head_shift + 1, head_shift + 2, head_shift + 3])
+
+
+@pytest.mark.parametrize("precision", ["f32", "bf16"])
+def test_minimal_ring_new_version_replaces_stale_snapshot(precision):
+    """Ring depth tau_j + 1: the slot written is the slot of V[0], read in the same pass."""
+    w = W.custom_workload("inplace", [[50_000, 17], [20_000], [4_000]], [2, 1, 0], 3, -1, precision=precision, seed=14)
+    plan, st, host = PU.load_workload(w, amplified=True, ring_depth=B.FERRET_RING_DEPTH_MINIMAL)
+    for j in range(3):
+        assert plan.stage_write_slot(j) == plan.stage_read_slots(j)[0]
+    st.step(w.lam, w.lr)
+    torch.cuda.synchronize()
+    PU.check_step_against_oracle(w, plan, st, host)
+
+
+@pytest.mark.parametrize("precision,depth", [("f32", 4), ("f32", 0), ("bf16", 4), ("bf16", 0)])
+def test_many_steps_with_warmup_and_wraparound(precision, depth):
+    """From a single pushed version through 2R+3 steps: warm-up staleness, eviction, wrap-around;
+    every step's new version is compared with the oracle's version store."""
+    tau = [3, 1, 0]
+    w = W.custom_workload("steps", [[20_000, 9], [6_000], [3_001]], tau, depth or 4, 2, precision=precision, seed=15)
+    plan = B.plan_for_workload(w, ring_depth=depth)
+    st = B.DeviceState(plan, PU.tensors_of(w))
+    ring = O.OracleRing(tau, 4 if depth else 99, 2, precision)   # oracle never needs more than tau+1
+    for j in range(3):
+        d = W.generate_stage(w, j, True, n_versions=1)
+        init = d.master if precision == "bf16" else d.versions[0]          # fp32 initial weights
+        src = torch.zeros(plan.flat_elems, dtype=torch.float32, device="cuda")
+        st.set_flat(src, j, init)
+        B.ferret_push_version(plan, st.ring, st.master, j, src)
+        torch.cuda.synchronize()
+        want0 = init.to(torch.bfloat16) if precision == "bf16" else init
+        assert torch.equal(st.get_version(j, 0), want0)
+        ring.push(j, want0, init if precision == "bf16" else None)
+    assert plan.get_state() == ([0, 0, 0], [1, 1, 1])
+    for step in range(11):
+        for j in range(3):
+            g = W.draw_grads(w, j, w.stage_numel()[j], amplified=True, step=step)
+            g = g.to(torch.bfloat16) if precision == "bf16" else g
+            st.set_flat(st.grads, j, g)
+            assert plan.stage_effective_staleness(j) == ring.effective_tau(j)
+        slots = [plan.stage_write_slot(j) for j in range(3)]
+        st.step(w.lam, w.lr)
+        torch.cuda.synchronize()
+        norms = st.norms.cpu().numpy()
+        for j in range(3):
+            g = st.get_flat(st.grads, j)
+            new, g_ref, n_ref = ring.step(j, g, np.float32(w.lam), np.float32(w.lr))
+            tag = f"step {step} stage {j}"
+            PU.assert_close_f32(st.get_flat(st.grad_out, j).numpy(), g_ref, tag + " g")
+            if precision == "f32":
+                got = st.get_version(j, slots[j]).numpy()
+                PU.assert_close_f32(got, new, tag + " version")
+                ring.versions[j][-1] = got.copy()          # keep both sides on identical inputs
+            else:
+                got = PU.bits_of(st.get_version(j, slots[j]))
+                PU.assert_bf16_within_one_ulp(got, new, tag + " version")
+                got_m = st.get_flat(st.master, j).numpy()
+                PU.assert_close_f32(got_m, ring.master[j], tag + " master")
+                ring.versions[j][-1] = got.copy()
+                ring.master[j] = got_m.copy()
+            np.testing.assert_allclose(norms[j], n_ref, rtol=PU.RTOL, atol=1e-30)
+        st.commit()
+    heads, valid = plan.get_state()
+    assert valid == [plan.stage_ring_depth(j) for j in range(3)]
+
+
+# ---- properties that hold at any size ---------------------------------------------------------
+def test_zero_lambda_and_zero_drift_leave_gradient_bit_exact():
+    w = W.make_workload(2)
+    plan, st, host = PU.load_workload(w, amplified=True)
+    st.step(0.0, w.lr)
+    torch.cuda.synchronize()
+    for j in range(w.n_stages):
+        assert torch.equal(st.get_flat(st.grad_out, j), host[j].grads)
+    # zero drift: every slot holds the same weights
+    for j in range(w.n_stages):
+        for s in range(w.ring_depth):
+            st.set_version(j, s, host[j].versions[-1])
+    st.step(w.lam, w.lr)
+    torch.cuda.synchronize()
+    norms = st.norms.cpu().numpy()
+    for j in range(w.n_stages):
+        assert torch.equal(st.get_flat(st.grad_out, j), host[j].grads)
+        want = host[j].versions[-1].double() - float(np.float32(w.lr)) * host[j].grads.double()
+        PU.assert_close_f32(st.get_version(j, plan.stage_write_slot(j)).numpy(), want.numpy(), "sgd")
+        assert norms[j][2] == 0.0 and norms[j][0] == norms[j][1]
+
+
+def test_outputs_do_not_depend_on_optional_outputs_or_grid():
+    w = W.custom_workload("grid", [[300_000, 40], [77_777]], [3, 1], 4, 2, seed=16)
+    results = []
+    for tuning, norms, gout in [(None, True, True), (dict(blocks_per_cu=-1), True, True),
+                                (dict(blocks_per_cu=1), False, False), (dict(blocks_per_cu=3), True, False),
+                                (dict(slot_align_elems=4096, slot_skew_elems=520), False, True)]:
+        plan, st, host = PU.load_workload(w, amplified=True, tuning=tuning)
+        st.step(w.lam, w.lr, norms=norms, grad_out=gout)
+        torch.cuda.synchronize()
+        results.append(([st.get_version(j, plan.stage_write_slot(j)) for j in range(2)],
+                        st.norms.cpu().clone() if norms else None))
+    for new, nrm in results[1:]:
+        for a, b in zip(new, results[0][0]):
+            assert torch.equal(a, b)
+        if nrm is not None:
+            assert torch.equal(nrm, results[0][1])      # per-chunk partials summed in chunk order
+
+
+def test_step_is_repeatable_and_does_not_touch_inputs():
+    w = W.custom_workload("repeat", [[100_000]], [2], 4, -1, seed=17)
+    plan, st, host = PU.load_workload(w, amplified=True)
+    ring_before = st.ring.clone()
+    st.step(w.lam, w.lr)
+    torch.cuda.synchronize()
+    first = st.ring.clone()
+    st.step(w.lam, w.lr)
+    torch.cuda.synchronize()
+    assert torch.equal(first, st.ring)
+    slot = plan.stage_write_slot(0)
+    for s in range(4):
+        if s != slot:
+            assert torch.equal(st.get_version(0, s), ring_before[plan.slot_offset(0, s):][:100_000].cpu())
+    assert torch.equal(st.get_flat(st.grads, 0), host[0].grads)
+
+
+def test_runs_on_a_side_stream():
+    w = W.custom_workload("stream", [[200_000], [50_000]], [1, 0], 2, 1, seed=18)
+    plan, st, host = PU.load_workload(w, amplified=True)
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    st.step(w.lam, w.lr, stream=s)
+    s.synchronize()
+    PU.check_step_against_oracle(w, plan, st, host)
+
+
+def test_nan_and_inf_propagate_like_the_oracle():
+    w = W.custom_workload("nonfinite", [[4096]], [2], 3, -1, seed=19)
+    plan, st, host = PU.load_workload(w, amplified=True)
+    g = host[0].grads.clone()
+    g[5], g[6], g[7] = float("nan"), float("inf"), float("-inf")
+    host[0].grads = g
+    st.set_flat(st.grads, 0, g)
+    st.step(w.lam, w.lr, norms=False)
+    torch.cuda.synchronize()
+    ref = PU.oracle_stage(w, host[0], 2, -1)
+    got_g = st.get_flat(st.grad_out, 0).numpy()
+    assert np.isnan(got_g[5]) and np.isnan(ref["g"][5])
+    PU.assert_close_f32(got_g, ref["g"], "g with non-finite entries")
+    PU.assert_close_f32(st.get_version(0, plan.stage_write_slot(0)).numpy(), ref["new"], "version with non-finite entries")
+
+
+# ---- push_version --------------------------------------------------------------------------------
+@pytest.mark.parametrize("precision", ["f32", "bf16"])
+def test_push_version_copies_rounds_and_advances(precision):
+    w = W.custom_workload("push", [[5000, 3], [2049]], [1, 0], 3, 1, precision=precision, seed=20)
+    plan = B.plan_for_workload(w)
+    st = B.DeviceState(plan, PU.tensors_of(w))
+    src = torch.randn(plan.flat_elems, device="cuda") * 0.05
+    # values exactly between two bf16 neighbours, to see ties-to-even on the device
+    src[:4] = torch.tensor([1.0 + 2.0 ** -8, 1.0 + 2.0 ** -7 + 2.0 ** -8, -(1.0 + 2.0 ** -8), 65280.0 + 128.0])
+    B.ferret_push_version(plan, st.ring, st.master, -1, src)
+    torch.cuda.synchronize()
+    assert plan.get_state() == ([0, 0], [1, 1])
+    for j in range(2):
+        n, fo = plan.stage_numel(j), plan.stage_flat_offset(j)
+        got = st.ring[plan.slot_offset(j, 0):][:n].cpu()
+        want = src[fo:fo + n].cpu()
+        if precision == "bf16":
+            want_bits = np.array([O.f32_to_bf16_bits(x) for x in want[:64].numpy()], dtype=np.uint16)
+            assert np.array_equal(PU.bits_of(got[:64]), want_bits)
+            assert torch.equal(got, want.to(torch.bfloat16))
+            assert torch.equal(st.master[fo:fo + n].cpu(), want)
+        else:
+            assert torch.equal(got, want)
+    # second push of one stage goes to slot 1 and leaves the other stage alone
+    B.ferret_push_version(plan, st.ring, None, 1, src * 2)
+    torch.cuda.synchronize()
+    assert plan.get_state() == ([0, 1], [1, 2])
+    n, fo = plan.stage_numel(1), plan.stage_flat_offset(1)
+    assert torch.equal(st.ring[plan.slot_offset(1, 1):][:n].float().cpu(),
+                       (src[fo:fo + n] * 2).to(st.storage).float().cpu())
+
+
+def test_copy_bytes():
+    a = torch.randn(3_000_001 * 4, device="cuda")
+    b = torch.zeros_like(a)
+    B.ferret_copy_bytes(b, a, a.numel() * 4)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)

@@ -1,0 +1,232 @@
+"""CPU-only tests of libferret's host side: the library loads and exports the whole C ABI,
+the bucket planner's layout, the ring bookkeeping, and every argument error that is detected
+before a HIP call.  No kernel is launched here."""
+import os
+import re
+
+import pytest
+
+from oracle import ferret_oracle as O
+from paper_2503_12053_amd import binding as B
+from paper_2503_12053_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2503_12053_amd import build
+    build.build(verbose=False)          # no-op when the library is newer than its sources
+    return B.load()
+
+
+def test_library_exports_every_declared_symbol(lib):
+    header = open(os.path.join(ROOT, "include", "ferret.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(ferret_[a-z0-9_]+)\s*\(", header))
+    assert {"ferret_plan_buckets", "ferret_push_version", "ferret_compensate_step"} <= declared
+    assert declared == set(B.SIGNATURES), declared ^ set(B.SIGNATURES)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert b"gfx950" in lib.ferret_version()
+
+
+def _plan(sizes_per_stage, tau, K=-1, R=None, prec=B.FERRET_F32, chunk=0, tuning=None):
+    tensors = [(n, j) for j, sizes in enumerate(sizes_per_stage) for n in sizes]
+    R = max(tau) + 1 if R is None else R
+    return B.ferret_plan_buckets(tensors, len(sizes_per_stage), tau, K, R, prec, chunk, tuning), tensors
+
+
+def test_layout_alignment_and_disjointness(lib):
+    sizes = [[1, 3, 1001, 64], [7], [4096, 5]]
+    plan, tensors = _plan(sizes, [2, 1, 0], R=3)
+    assert plan.n_stages == 3 and plan.n_tensors == 7
+    assert plan.total_params == sum(n for n, _ in tensors)
+    # tensor offsets: aligned, in order, non-overlapping inside the stage
+    i = 0
+    for j, ss in enumerate(sizes):
+        end = 0
+        for n in ss:
+            off = plan.tensor_offset(i)
+            assert off % B.FERRET_ALIGN_ELEMS == 0 and off >= end
+            end = off + n
+            i += 1
+        assert plan.stage_params(j) == sum(ss)
+        assert plan.stage_numel(j) >= end and plan.stage_numel(j) % B.FERRET_ALIGN_ELEMS == 0
+        assert plan.stage_numel(j) - end < B.FERRET_ALIGN_ELEMS
+    # flat and ring regions: aligned to 16 bytes at least, disjoint, inside the totals
+    flat, ring = [], []
+    for j in range(3):
+        fo, n = plan.stage_flat_offset(j), plan.stage_numel(j)
+        assert fo % 4 == 0
+        flat.append((fo, fo + n))
+        stride, R = plan.stage_slot_stride(j), plan.stage_ring_depth(j)
+        assert stride >= n and stride % 4 == 0 and R == 3
+        for s in range(R):
+            ring.append((plan.slot_offset(j, s), plan.slot_offset(j, s) + n))
+    for regions, total in ((flat, plan.flat_elems), (ring, plan.ring_elems)):
+        regions.sort()
+        assert regions[0][0] >= 0 and regions[-1][1] <= total
+        for a, b in zip(regions, regions[1:]):
+            assert a[1] <= b[0]
+    assert plan.ring_bytes == plan.ring_elems * 4 and plan.grad_bytes == plan.flat_elems * 4
+    assert plan.master_bytes == plan.flat_elems * 4
+    assert plan.workspace_bytes >= plan.n_chunks * 12
+
+
+def test_chunks_never_cross_stage_boundaries(lib):
+    plan, _ = _plan([[5000], [100], [3000, 3000]], [2, 1, 0], R=3, chunk=1024)
+    per_stage = [-(-plan.stage_numel(j) // 1024) for j in range(3)]
+    assert plan.chunk_elems == 1024 and plan.n_chunks == sum(per_stage)
+    assert per_stage == [5, 1, 6]
+
+
+def test_bf16_plan_sizes(lib):
+    plan, _ = _plan([[100], [200]], [1, 0], R=2, prec=B.FERRET_BF16_MASTER_F32)
+    assert plan.precision == B.FERRET_BF16_MASTER_F32
+    assert plan.ring_bytes == plan.ring_elems * 2 and plan.grad_bytes == plan.flat_elems * 2
+    assert plan.master_bytes == plan.flat_elems * 4
+    assert plan.chunk_elems % 2048 == 0
+
+
+def test_minimal_ring_depth_is_paper_count(lib):
+    """Stage j of a P-stage pipeline keeps P-j versions (T2 with one accumulation step)."""
+    P = 5
+    tau = [P - 1 - j for j in range(P)]
+    plan, _ = _plan([[64]] * P, tau, R=B.FERRET_RING_DEPTH_MINIMAL)
+    assert [plan.stage_ring_depth(j) for j in range(P)] == [P - j for j in range(P)]
+
+
+def test_tuning_changes_slot_stride_only(lib):
+    base, _ = _plan([[1000], [1000]], [1, 0], R=2)
+    tuned, _ = _plan([[1000], [1000]], [1, 0], R=2, tuning=dict(slot_align_elems=1024, slot_skew_elems=32))
+    assert base.stage_slot_stride(0) == 1024            # 1000 rounded up to the default 64
+    assert tuned.stage_slot_stride(0) == 1024 + 32
+    assert tuned.stage_numel(0) == base.stage_numel(0) == 1000
+    assert tuned.flat_elems == base.flat_elems
+
+
+@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5])
+def test_benchmark_workload_plans(lib, idx):
+    w = W.make_workload(idx)
+    plan = B.plan_for_workload(w)
+    assert plan.total_params == w.numel
+    assert [plan.stage_params(j) for j in range(w.n_stages)] == w.stage_numel()
+    # with every slot valid the step reads K'+1 versions per stage
+    R = w.ring_depth
+    plan.set_state([R - 1] * w.n_stages, [R] * w.n_stages)
+    elt = 4 if w.precision == "f32" else 2
+    want = 0
+    for j, n in enumerate(w.stage_numel()):
+        Kp = O.effective_iters(w.n_iters, w.staleness[j])
+        assert plan.stage_effective_iters(j) == Kp
+        per = elt * (Kp + 3) + (8 if w.precision == "bf16" else 0)
+        want += per * n
+    assert plan.step_bytes == want
+    if idx == 4:
+        assert want == 1_898_268_384            # the configuration the bandwidth target is quoted on
+
+
+def test_read_slots_follow_segment_boundaries(lib):
+    for tau in range(0, 9):
+        for K in (-1, 0, 1, 2, 3, 4):
+            for R in (tau + 1, tau + 3):
+                plan, _ = _plan([[64]], [tau], K=K, R=R)
+                for head in {0, R - 1, R // 2}:
+                    plan.set_state([head], [R])
+                    bounds = O.segment_boundaries(tau, K)      # [tau] when there is no iteration
+                    want = [(head - (tau - s)) % R for s in bounds]
+                    assert plan.stage_read_slots(0) == want
+                    assert plan.stage_write_slot(0) == (head + 1) % R
+                    # the slot written may coincide only with the oldest version of a full-depth window
+                    if (head + 1) % R in want:
+                        assert R == tau + 1 and want.index((head + 1) % R) == 0
+
+
+def test_warmup_staleness_and_commit_rules(lib):
+    plan, _ = _plan([[64]], [3], K=-1, R=4)
+    heads, valid = plan.get_state()
+    assert heads == [0] and valid == [0]
+    assert plan.stage_write_slot(0) == 0
+    # nothing pushed yet: a step is a state error, and so is a commit
+    rc = lib.ferret_compensate_step(plan.handle, 16, 16, None, 0.5, 0.01, None, None, None, None)
+    assert rc == B.FERRET_ESTATE and "no weight version" in B.last_error()
+    rc = lib.ferret_push_version(plan.handle, 16, None, -1, None, None)
+    assert rc == B.FERRET_ESTATE and "without a step" in B.last_error()
+    for held in range(1, 6):
+        plan.set_state([(held - 1) % 4], [min(held, 4)])
+        assert plan.stage_effective_staleness(0) == min(3, held - 1)
+
+
+def test_set_state_validation(lib):
+    plan, _ = _plan([[64], [64]], [1, 0], R=2)
+    with pytest.raises(B.FerretError) as e:
+        plan.set_state([2, 0], [1, 1])
+    assert e.value.status == B.FERRET_EINVAL
+    with pytest.raises(B.FerretError):
+        plan.set_state([0, 0], [3, 1])
+    plan.set_state([1, 0], [2, 1])
+    assert plan.get_state() == ([1, 0], [2, 1])
+
+
+BAD_PLANS = [
+    dict(tensors=[], n_stages=1, tau=[0]),
+    dict(tensors=[(10, 0)], n_stages=0, tau=[]),
+    dict(tensors=[(10, 0)], n_stages=B.FERRET_MAX_STAGES + 1, tau=[0] * (B.FERRET_MAX_STAGES + 1)),
+    dict(tensors=[(0, 0)], n_stages=1, tau=[0]),
+    dict(tensors=[(10, 1)], n_stages=2, tau=[0, 0]),                # stage 0 empty
+    dict(tensors=[(10, 0), (10, 2)], n_stages=3, tau=[0, 0, 0]),    # stage 1 skipped
+    dict(tensors=[(10, 1), (10, 0)], n_stages=2, tau=[0, 0]),       # decreasing
+    dict(tensors=[(10, 0)], n_stages=2, tau=[0, 0]),                # last stage empty
+    dict(tensors=[(10, 0)], n_stages=1, tau=[-1]),
+    dict(tensors=[(10, 0)], n_stages=1, tau=[2], R=2),              # tau >= ring depth
+    dict(tensors=[(10, 0)], n_stages=1, tau=[0], K=-2),
+    dict(tensors=[(10, 0)], n_stages=1, tau=[0], R=-1),
+    dict(tensors=[(10, 0)], n_stages=1, tau=[0], prec=7),
+    dict(tensors=[(10, 0)], n_stages=1, tau=[0], chunk=1000),
+    dict(tensors=[(10, 0)], n_stages=1, tau=[0], tuning=dict(slot_align_elems=100)),
+    dict(tensors=[(10, 0)], n_stages=1, tau=[0], tuning=dict(slot_skew_elems=3)),
+    dict(tensors=[(10, 0)], n_stages=1, tau=[0], tuning=dict(reserved=1)),
+]
+
+
+@pytest.mark.parametrize("bad", BAD_PLANS)
+def test_plan_rejects_bad_arguments(lib, bad):
+    with pytest.raises(B.FerretError) as e:
+        B.ferret_plan_buckets(bad["tensors"], bad["n_stages"], bad["tau"], bad.get("K", 1), bad.get("R", 1),
+                              bad.get("prec", B.FERRET_F32), bad.get("chunk", 0), bad.get("tuning"))
+    assert e.value.status == B.FERRET_EINVAL and e.value.message
+
+
+def test_step_and_push_argument_errors(lib):
+    plan, _ = _plan([[64]], [1], R=2)
+    plan.set_state([0], [1])
+    step = lib.ferret_compensate_step
+    h = plan.handle
+    assert step(None, 16, 16, None, 0.5, 0.01, None, None, None, None) == B.FERRET_EINVAL
+    assert step(h, None, 16, None, 0.5, 0.01, None, None, None, None) == B.FERRET_EINVAL
+    assert step(h, 16, None, None, 0.5, 0.01, None, None, None, None) == B.FERRET_EINVAL
+    assert step(h, 24, 16, None, 0.5, 0.01, None, None, None, None) == B.FERRET_EINVAL     # misaligned ring
+    assert "aligned" in B.last_error()
+    assert step(h, 16, 16, 32, 0.5, 0.01, None, None, None, None) == B.FERRET_EINVAL       # master on fp32 plan
+    assert step(h, 16, 16, None, 0.5, 0.01, 32, None, None, None) == B.FERRET_EINVAL       # norms without workspace
+    push = lib.ferret_push_version
+    assert push(None, 16, None, -1, 16, None) == B.FERRET_EINVAL
+    assert push(h, 16, None, 5, 16, None) == B.FERRET_EINVAL
+    assert push(h, None, None, -1, 16, None) == B.FERRET_EINVAL
+    assert push(h, 16, None, -1, 8, None) == B.FERRET_EINVAL                               # misaligned src
+    assert push(h, 16, 32, -1, 16, None) == B.FERRET_EINVAL                                # master on fp32 plan
+    mixed, _ = _plan([[64]], [1], R=2, prec=B.FERRET_BF16_MASTER_F32)
+    mixed.set_state([0], [1])
+    assert step(mixed.handle, 16, 16, None, 0.5, 0.01, None, None, None, None) == B.FERRET_EINVAL
+    assert "master" in B.last_error()
+    assert lib.ferret_copy_bytes(16, 16, 8, None) == B.FERRET_EINVAL
+    assert lib.ferret_copy_bytes(16, 16, 0, None) == B.FERRET_OK
+
+
+def test_queries_on_null_or_out_of_range(lib):
+    assert lib.ferret_plan_n_stages(None) == -1
+    assert lib.ferret_plan_ring_bytes(None) == 0
+    plan, _ = _plan([[64]], [0], R=1)
+    assert plan.stage_numel(3) == -1 and plan.tensor_offset(-1) == -1
+    lib.ferret_plan_destroy(None)
