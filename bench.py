@@ -1,0 +1,213 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused compensate + update step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 4] [--no-norms] [--no-cpu-baseline]
+
+A "step" is one pass of the whole path over every stage of the workload:
+ferret_compensate_step (gradient load, K'+1 version loads, K' iterations, update, store of the
+new version into the next ring slot, per-stage norms) followed by ferret_push_version(src=NULL)
+(head advance).  Heads advance every step, so successive steps touch different ring slots.
+
+Inputs are seeded and synthetic (paper_2503_12053_amd.workloads), generated on the host and
+resident in HBM before the timed region.  One JSON line goes to stdout; context goes to stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import statistics
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def read_traffic(workload_name: str):
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE), if a summary
+    for this workload has been committed under profiles/."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload_name}.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        if line.startswith("traffic_bytes_per_launch:"):
+            return float(line.split(":")[1])
+    return None
+
+
+def cpu_baseline(w, host, plan, budget_s=20.0):
+    """Time the oracle (as it stands) on the host cores over one step of the same workload."""
+    import numpy as np
+    from oracle import ferret_oracle as O
+    cores = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
+    cores = min(cores, int(os.environ.get("OMP_NUM_THREADS", cores)))
+
+    def one_step(n_threads, stages):
+        t0 = time.perf_counter()
+        n = 0
+        for j in stages:
+            tau = plan.stage_effective_staleness(j)
+            window = host[j].versions[len(host[j].versions) - 1 - tau:]
+            if w.precision == "f32":
+                O.compensate_stage_f32(window, host[j].grads, w.n_iters, np.float32(w.lam), np.float32(w.lr),
+                                       n_threads=n_threads, want_g=False)
+            else:
+                O.compensate_stage_bf16(window, host[j].grads, host[j].master, w.n_iters, np.float32(w.lam),
+                                        np.float32(w.lr), n_threads=n_threads, want_g=False)
+            n += w.stage_numel()[j]
+        return time.perf_counter() - t0, n
+
+    # bounded sample: whole stages, as many as fit the time budget (probe with the smallest stage)
+    order = sorted(range(w.n_stages), key=lambda j: w.stage_numel()[j])
+    t_probe, n_probe = one_step(1, order[:1])
+    rate1 = n_probe / t_probe
+    stages, acc = [], 0
+    for j in range(w.n_stages):
+        if (acc + w.stage_numel()[j]) / rate1 > budget_s * 0.5 and stages:
+            break
+        stages.append(j)
+        acc += w.stage_numel()[j]
+    t1, n1 = one_step(1, stages)
+    tn, nn = one_step(cores, stages)
+    sample = (f"one step of stages {stages[0]}..{stages[-1]} of {w.name} ({n1} of {w.numel} parameters), "
+              f"fp64 oracle, 1 thread {t1:.2f} s, {cores} threads {tn:.2f} s")
+    return {"value": nn / tn, "unit": "params/s", "cores": cores, "kind": "oracle", "sample": sample,
+            "single_thread_value": n1 / t1}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=4, help="workload 1..5 (4 = the one the metric is quoted on)")
+    ap.add_argument("--no-norms", action="store_true", help="skip the per-stage norms (not the default path)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--chunk-elems", type=int, default=0)
+    ap.add_argument("--blocks-per-cu", type=int, default=0)
+    ap.add_argument("--slot-align", type=int, default=0)
+    ap.add_argument("--slot-skew", type=int, default=0)
+    ap.add_argument("--iters", type=int, default=None, help="override K (-1 = one iteration per version step)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build measures one GPU only (the path has no cross-GPU step); run with --gpus 1")
+        sys.exit(2)
+
+    import torch
+    from paper_2503_12053_amd import binding as B
+    from paper_2503_12053_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible")
+        sys.exit(2)
+    B.load()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    w = W.make_workload(args.config)
+    if args.iters is not None:
+        w.n_iters = args.iters
+    tuning = None
+    if args.blocks_per_cu or args.slot_align or args.slot_skew:
+        tuning = dict(blocks_per_cu=args.blocks_per_cu, slot_align_elems=args.slot_align,
+                      slot_skew_elems=args.slot_skew)
+    plan = B.plan_for_workload(w, chunk_elems=args.chunk_elems, tuning=tuning)
+    st = B.DeviceState(plan, [(n, s) for _, n, s in w.tensors], device=dev, want_grad_out=False,
+                       want_norms=not args.no_norms)
+    t0 = time.perf_counter()
+    host, heads = [], []
+    for j in range(w.n_stages):
+        d = W.generate_stage(w, j)
+        heads.append(st.load_versions(j, d.versions))
+        st.set_flat(st.grads, j, d.grads)
+        if d.master is not None:
+            st.set_flat(st.master, j, d.master)
+        host.append(d)
+    plan.set_state(heads, [w.ring_depth] * w.n_stages)
+    torch.cuda.synchronize()
+    step_bytes = plan.step_bytes
+    log(f"workload {w.name}: {w.numel} parameters, {w.n_stages} stages, ring {plan.ring_bytes / 1e9:.2f} GB, "
+        f"{plan.n_chunks} chunks of {plan.chunk_elems}, algorithmic bytes/step {step_bytes} "
+        f"(inputs ready in {time.perf_counter() - t0:.1f} s)")
+
+    norms = not args.no_norms
+
+    def one_step():
+        st.step(w.lam, w.lr, norms=norms, grad_out=False)
+        st.commit()
+
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+
+    B.ferret_profile_begin(args.steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    kernel_ms = B.ferret_profile_end(args.steps)
+
+    ms_per_step = elapsed * 1e3 / args.steps
+    params_per_s = w.numel / (elapsed / args.steps)
+    k_avg = statistics.fmean(kernel_ms)
+    k_med = statistics.median(kernel_ms)
+    achieved = step_bytes / (k_avg * 1e-3) / 1e9
+    log(f"step: {ms_per_step * 1e3:.1f} us wall per step; fused kernel avg {k_avg * 1e3:.1f} us, median "
+        f"{k_med * 1e3:.1f} us, min {min(kernel_ms) * 1e3:.1f} us -> {achieved:.0f} GB/s algorithmic "
+        f"({achieved / HBM_PEAK_GBS:.1%} of {HBM_PEAK_GBS:.0f} GB/s)")
+
+    # context: plain copy through the library's copy kernel (read + write of the same byte count)
+    n_copy = min(plan.ring_bytes // 2, 1 << 30) // 16 * 16
+    src_t = st.ring.view(torch.uint8)[:n_copy]
+    dst_t = st.ring.view(torch.uint8)[plan.ring_bytes - n_copy:] if plan.ring_bytes >= 2 * n_copy else torch.empty(n_copy, dtype=torch.uint8, device=dev)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    for _ in range(3):
+        B.ferret_copy_bytes(dst_t, src_t, n_copy)
+    ev[0].record()
+    for _ in range(10):
+        B.ferret_copy_bytes(dst_t, src_t, n_copy)
+    ev[1].record()
+    torch.cuda.synchronize()
+    copy_gbs = 2 * n_copy * 10 / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e9
+    log(f"copy kernel ceiling: {copy_gbs:.0f} GB/s (read+write, {n_copy / 1e6:.0f} MB)")
+
+    result = {
+        "metric": "compensated_params_per_sec",
+        "value": params_per_s,
+        "unit": "params/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32" if w.precision == "f32" else "bf16 storage, f32 arithmetic",
+        "data": "synthetic",
+        "config": {"workload": w.name, "params": w.numel, "stages": w.n_stages, "staleness": w.staleness,
+                   "ring_depth": w.ring_depth, "n_iters": w.n_iters, "lambda": w.lam, "lr": w.lr,
+                   "norms": norms, "chunk_elems": plan.chunk_elems, "algorithmic_bytes_per_step": step_bytes},
+        "hbm_gbs_wall": step_bytes / (elapsed / args.steps) / 1e9,
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic(w.name),
+                     "kernel": "ferret::step_kernel", "kernel_avg_us": k_avg * 1e3, "kernel_median_us": k_med * 1e3,
+                     "copy_kernel_gbs": copy_gbs},
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, host, plan)
+        log("cpu baseline:", result["cpu_baseline"]["sample"])
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

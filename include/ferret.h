@@ -209,6 +209,18 @@ const char *ferret_version(void);
  * launch shape as the step; not part of the method. */
 ferret_status ferret_copy_bytes(void *dst, const void *src, size_t n_bytes, void *hip_stream);
 
+/* ---- measurement ------------------------------------------------------------------------------ */
+/* Per-launch timing of the fused step kernel with HIP events recorded on the step's own stream,
+ * immediately before and after that kernel (the norms' finalize kernel is outside the pair).
+ * begin: create `capacity` event pairs; from then on every ferret_compensate_step of this process
+ *        records one pair until the capacity is used up.
+ * end:   wait for the last recorded pair, write the durations in milliseconds (launch order) to the
+ *        host array ms_out[0 .. min(cap, recorded)), store the number recorded in *n_out, destroy the
+ *        events.  FERRET_ESTATE if begin was not called.
+ * Process-wide, not thread-safe; meant for benchmarks. */
+ferret_status ferret_profile_begin(int32_t capacity);
+ferret_status ferret_profile_end(float *ms_out, int32_t cap, int32_t *n_out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -90,6 +90,8 @@ SIGNATURES = {
     "ferret_last_error": (c_char_p, []),
     "ferret_version": (c_char_p, []),
     "ferret_copy_bytes": (c_int32, [_P, _P, c_size_t, _P]),
+    "ferret_profile_begin": (c_int32, [c_int32]),
+    "ferret_profile_end": (c_int32, [POINTER(c_float), c_int32, POINTER(c_int32)]),
 }
 
 _lib = None
@@ -174,6 +176,18 @@ def ferret_compensate_step(plan: "Plan", ring, grads, master, lam: float, lr: fl
 
 def ferret_copy_bytes(dst, src, n_bytes: int, stream=None) -> None:
     _check(load().ferret_copy_bytes(_ptr(dst), _ptr(src), n_bytes, _stream(stream)))
+
+
+def ferret_profile_begin(capacity: int) -> None:
+    _check(load().ferret_profile_begin(capacity))
+
+
+def ferret_profile_end(capacity: int) -> List[float]:
+    """Durations (ms) of the step-kernel launches recorded since ferret_profile_begin."""
+    buf = (c_float * max(capacity, 1))()
+    n = c_int32(0)
+    _check(load().ferret_profile_end(buf, capacity, byref(n)))
+    return [float(buf[i]) for i in range(min(n.value, capacity))]
 
 
 class Plan:

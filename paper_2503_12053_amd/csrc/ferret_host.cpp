@@ -401,4 +401,20 @@ ferret_status ferret_copy_bytes(void *dst, const void *src, size_t n_bytes, void
     return FERRET_OK;
 }
 
+ferret_status ferret_profile_begin(int32_t capacity) {
+    if (capacity < 1 || capacity > (1 << 20)) { set_error("profile_begin: capacity = %d", capacity); return FERRET_EINVAL; }
+    int err = profile_begin(capacity);
+    if (err < 0) { set_error("profile_begin: already profiling"); return FERRET_ESTATE; }
+    if (err) { set_error("profile_begin: %s", device_error_string(err)); return FERRET_EDEVICE; }
+    return FERRET_OK;
+}
+
+ferret_status ferret_profile_end(float *ms_out, int32_t cap, int32_t *n_out) {
+    if (!n_out || cap < 0 || (cap > 0 && !ms_out)) { set_error("profile_end: bad arguments"); return FERRET_EINVAL; }
+    int err = profile_end(ms_out, cap, n_out);
+    if (err < 0) { set_error("profile_end: profile_begin was not called"); return FERRET_ESTATE; }
+    if (err) { set_error("profile_end: %s", device_error_string(err)); return FERRET_EDEVICE; }
+    return FERRET_OK;
+}
+
 }  // extern "C"

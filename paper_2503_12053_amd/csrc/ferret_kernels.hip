@@ -24,6 +24,8 @@
 //   * no matrix cores: there is no contraction anywhere on this path.
 #include <hip/hip_runtime.h>
 
+#include <vector>
+
 #include "ferret_internal.h"
 
 namespace ferret {
@@ -437,6 +439,45 @@ __global__ void __launch_bounds__(kThreads) copy_kernel(uint4 *dst, const uint4 
     if (i < n_vecs) dst[i] = src[i];
 }
 
+// ---- per-launch event timing of the step kernel ---------------------------------------------------
+struct Profiler {
+    std::vector<hipEvent_t> start, stop;
+    int32_t used = 0;
+    bool on = false;
+};
+static Profiler g_prof;
+
+int profile_begin(int32_t capacity) {
+    if (g_prof.on) return -1;
+    g_prof.start.assign(capacity, nullptr);
+    g_prof.stop.assign(capacity, nullptr);
+    for (int32_t i = 0; i < capacity; ++i) {
+        hipError_t e = hipEventCreate(&g_prof.start[i]);
+        if (e == hipSuccess) e = hipEventCreate(&g_prof.stop[i]);
+        if (e != hipSuccess) return (int)e;
+    }
+    g_prof.used = 0;
+    g_prof.on = true;
+    return 0;
+}
+
+int profile_end(float *ms_out, int32_t cap, int32_t *n_out) {
+    if (!g_prof.on) return -1;
+    hipError_t e = hipSuccess;
+    if (g_prof.used > 0) e = hipEventSynchronize(g_prof.stop[g_prof.used - 1]);
+    for (int32_t i = 0; i < g_prof.used && i < cap && e == hipSuccess; ++i)
+        e = hipEventElapsedTime(&ms_out[i], g_prof.start[i], g_prof.stop[i]);
+    *n_out = g_prof.used;
+    for (size_t i = 0; i < g_prof.start.size(); ++i) {
+        if (g_prof.start[i]) (void)hipEventDestroy(g_prof.start[i]);
+        if (g_prof.stop[i]) (void)hipEventDestroy(g_prof.stop[i]);
+    }
+    g_prof.start.clear();
+    g_prof.stop.clear();
+    g_prof.on = false;
+    return (int)e;
+}
+
 // ---- launchers ------------------------------------------------------------------------------------
 static int g_cu_count[64];   // per device ordinal, 0 = not queried yet
 
@@ -489,8 +530,11 @@ int launch_step(const ferret_plan &plan, const StepArgs &a, float *norms_out, vo
     bool streamed = false;
     for (uint32_t j = 0; j < a.n_stages; ++j) streamed |= a.stage[j].kp + 1 > kMaxUnrolledVersions;
     const bool norms = norms_out != nullptr, gout = a.grad_out != nullptr;
+    const bool timed = g_prof.on && g_prof.used < (int32_t)g_prof.start.size();
+    if (timed) (void)hipEventRecord(g_prof.start[g_prof.used], st);
     hipError_t e = plan.prec == FERRET_F32 ? launch_step_typed<F32Store>(a, streamed, norms, gout, grid, st)
                                            : launch_step_typed<Bf16Store>(a, streamed, norms, gout, grid, st);
+    if (timed) (void)hipEventRecord(g_prof.stop[g_prof.used++], st);
     if (e != hipSuccess) return (int)e;
     if (norms) {
         hipLaunchKernelGGL(norms_finalize_kernel, dim3(a.n_stages), dim3(kThreads), 0, st, a, norms_out);
