@@ -96,6 +96,8 @@ def main():
     ap.add_argument("--slot-align", type=int, default=0)
     ap.add_argument("--slot-skew", type=int, default=0)
     ap.add_argument("--iters", type=int, default=None, help="override K (-1 = one iteration per version step)")
+    ap.add_argument("--no-kernel-events", action="store_true",
+                    help="do not record per-launch HIP events (roofline is then taken from wall time)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build measures one GPU only (the path has no cross-GPU step); run with --gpus 1")
@@ -148,14 +150,15 @@ def main():
         one_step()
     torch.cuda.synchronize()
 
-    B.ferret_profile_begin(args.steps)
+    if not args.no_kernel_events:
+        B.ferret_profile_begin(args.steps)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
         one_step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    kernel_ms = B.ferret_profile_end(args.steps)
+    kernel_ms = B.ferret_profile_end(args.steps) if not args.no_kernel_events else [elapsed * 1e3 / args.steps]
 
     ms_per_step = elapsed * 1e3 / args.steps
     params_per_s = w.numel / (elapsed / args.steps)

@@ -82,9 +82,10 @@ typedef struct {
     int64_t slot_align_elems;  /* slot stride is rounded up to a multiple of this (multiple of 64) */
     int64_t slot_skew_elems;   /* then this is added (multiple of 8): de-phases the streams that
                                   read the same element of different slots */
-    int32_t blocks_per_cu;     /* >0: persistent grid of blocks_per_cu * (number of CUs) workgroups;
-                                  <0: one workgroup per chunk; 0: default */
-    int32_t reserved;          /* must be 0 */
+    int32_t blocks_per_cu;     /* >0: persistent grid of blocks_per_cu * (number of CUs) workgroups with
+                                  the stage table staged in LDS; <0: one workgroup per chunk; 0: default */
+    int32_t resident_cap;      /* >0: at most this many workgroups resident per CU (enforced by reserving
+                                  LDS that the kernel does not use); <0: no cap; 0: default */
 } ferret_tuning;
 
 typedef struct ferret_plan ferret_plan;   /* opaque; host memory; owned by the caller via destroy */

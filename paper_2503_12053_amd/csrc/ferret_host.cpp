@@ -92,16 +92,17 @@ ferret_status ferret_plan_buckets_tuned(const ferret_tensor *tensors, int32_t n_
     }
     const int64_t vec = vec_elems(prec);
     const int64_t chunk_unit = kThreads * vec;                 // one vector per thread
-    if (chunk_elems == 0) chunk_elems = chunk_unit * 8;
-    if (chunk_elems < 0 || chunk_elems % chunk_unit != 0 || chunk_elems > (int64_t(1) << 30)) {
-        set_error("plan: chunk_elems = %lld, need a positive multiple of %lld", (long long)chunk_elems,
+    if (chunk_elems == 0) chunk_elems = chunk_unit;          // one 16-byte vector per lane per stream (measured best)
+    if (chunk_elems < 0 || chunk_elems % chunk_unit != 0 || chunk_elems > (int64_t(1) << 24)) {   // lanes address a chunk with 32-bit byte offsets
+        set_error("plan: chunk_elems = %lld, need a positive multiple of %lld up to 2^24", (long long)chunk_elems,
                   (long long)chunk_unit);
         return FERRET_EINVAL;
     }
     int64_t slot_align = kDefaultSlotAlign, slot_skew = 0;
-    int32_t blocks_per_cu = 0;
+    int32_t blocks_per_cu = 0, resident_cap = 0;
     if (tuning) {
-        if (tuning->reserved != 0) { set_error("plan: tuning.reserved must be 0"); return FERRET_EINVAL; }
+        resident_cap = tuning->resident_cap;
+        if (resident_cap > 32) { set_error("plan: resident_cap = %d, need <= 32", resident_cap); return FERRET_EINVAL; }
         if (tuning->slot_align_elems) slot_align = tuning->slot_align_elems;
         slot_skew = tuning->slot_skew_elems;
         blocks_per_cu = tuning->blocks_per_cu;
@@ -142,6 +143,7 @@ ferret_status ferret_plan_buckets_tuned(const ferret_tensor *tensors, int32_t n_
     p->n_iters = n_iters;
     p->chunk_elems = chunk_elems;
     p->blocks_per_cu = blocks_per_cu;
+    p->resident_cap = resident_cap;
 
     // tensors -> stage buckets
     int32_t prev_stage = 0;
@@ -383,6 +385,8 @@ ferret_status ferret_compensate_step(const ferret_plan *plan, void *ring, const 
     a.chunk_elems = (uint32_t)plan->chunk_elems;
     a.pad_ = 0;
     fill_step_descs(*plan, a.stage);
+    for (uint32_t j = 0; j < FERRET_MAX_STAGES; ++j)
+        a.chunk_begin[j] = j < a.n_stages ? a.stage[j].chunk_begin : UINT32_MAX;
     int err = launch_step(*plan, a, norms_out, hip_stream);
     if (err) { set_error("compensate_step: launch failed: %s", device_error_string(err)); return FERRET_EDEVICE; }
     // bookkeeping only: remembers that slot head+1 now holds an uncommitted version

@@ -32,13 +32,16 @@ struct StepArgs {
     const void *grads;
     float *master;
     float *grad_out;   // nullable
-    float *partials;   // float[n_chunks][3], nullable
+    float *partials;   // float[3][n_chunks] (three series, each contiguous), nullable
     float lambda;
     float lr;
     uint32_t n_stages;
     uint32_t n_chunks;
     uint32_t chunk_elems;
     uint32_t pad_;
+    // chunk_begin of every stage again, densely packed (unused entries = UINT32_MAX), so that a
+    // workgroup can find its chunk's stage with a few wide scalar loads
+    uint32_t chunk_begin[FERRET_MAX_STAGES];
     StageDesc stage[FERRET_MAX_STAGES];
 };
 static_assert(sizeof(StepArgs) <= 3400, "StepArgs must fit the kernel-argument segment");
@@ -85,6 +88,7 @@ struct ferret_plan {
     int64_t ring_elems = 0;
     int64_t total_params = 0;
     int32_t blocks_per_cu = 0;
+    int32_t resident_cap = 0;
 };
 
 namespace ferret {

@@ -30,12 +30,48 @@
 
 namespace ferret {
 
-constexpr int kThreads = 256;
+#ifndef FERRET_THREADS
+#define FERRET_THREADS 256
+#endif
+constexpr int kThreads = FERRET_THREADS;
 constexpr int kWaves = kThreads / 64;
-constexpr int kUnroll = 2;          // 16-byte vectors per lane per stream in flight
-constexpr int kMaxUnrolledVersions = 5;   // K' <= 4 runs fully unrolled
+#ifndef FERRET_UNROLL
+#define FERRET_UNROLL 1
+#endif
+#ifndef FERRET_NT
+#define FERRET_NT 3                 // bit 0: non-temporal loads, bit 1: non-temporal stores
+#endif
+constexpr int kUnroll = FERRET_UNROLL;   // 16-byte vectors per lane per stream in flight
+constexpr int kUnrolledItersSmall = 4;    // LEVEL 0 kernels: every stage has K' <= 4
+constexpr int kUnrolledItersMid = 8;      // LEVEL 1 kernels: K' <= 8; LEVEL 2 adds the streamed path for any K'
+constexpr int kDefaultResidentCapF32 = 4;   // workgroups per CU, see reserve_lds_for_cap
+constexpr int kDefaultResidentCapBf16 = 3;
+constexpr uint64_t kCapThresholdBytes = 512ull << 20;   // K' <= 4 runs fully unrolled
+
+// 16-byte vectors as clang vector types (so that the non-temporal builtins accept them)
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef uint32_t v4u __attribute__((ext_vector_type(4)));
 
 // ---- small device helpers ---------------------------------------------------------------------
+template <typename T>
+__device__ __forceinline__ T ld(const T *p) {
+#if FERRET_NT & 1
+    return __builtin_nontemporal_load(p);
+#else
+    return *p;
+#endif
+}
+template <typename T>
+__device__ __forceinline__ void st(T *p, const T &v) {
+#if FERRET_NT & 2
+    __builtin_nontemporal_store(v, p);
+#else
+    *p = v;
+#endif
+}
+__device__ __forceinline__ v4f make_v4f(float a, float b, float c, float d) {
+    v4f r; r.x = a; r.y = b; r.z = c; r.w = d; return r;
+}
 __device__ __forceinline__ uint32_t uniform(uint32_t x) { return __builtin_amdgcn_readfirstlane(x); }
 __device__ __forceinline__ uint64_t uniform(uint64_t x) {
     uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)x);
@@ -57,14 +93,14 @@ __device__ __forceinline__ uint32_t bf16_pack(float lo, float hi) { return bf16_
 
 // One 16-byte vector of the storage type, widened to fp32 lanes.
 struct F32Store {
-    using Raw = float4;
+    using Raw = v4f;
     static constexpr int kElems = 4;
     __device__ static __forceinline__ void widen(const Raw &r, float (&x)[kElems]) {
         x[0] = r.x; x[1] = r.y; x[2] = r.z; x[3] = r.w;
     }
 };
 struct Bf16Store {
-    using Raw = uint4;
+    using Raw = v4u;
     static constexpr int kElems = 8;
     __device__ static __forceinline__ void widen(const Raw &r, float (&x)[kElems]) {
         x[0] = bf16_lo(r.x); x[1] = bf16_hi(r.x); x[2] = bf16_lo(r.y); x[3] = bf16_hi(r.y);
@@ -77,21 +113,32 @@ __device__ __forceinline__ float approximator(float g, float lambda, float v_new
     return fmaf(lambda * g * g, v_new - v_old, g);
 }
 
-// Everything a lane needs to know about the chunk it works on (all wave-uniform).
-template <typename S, int NV>
+// Everything a lane needs to know about the chunk it works on.  All pointers are wave-uniform
+// (they live in scalar registers); lanes add a 32-bit byte offset, which is the addressing form
+// the global load/store instructions take directly.
+template <int NV>
 struct ChunkPtrs {
-    const typename S::Raw *g;                 // gradient
-    const typename S::Raw *v[NV];             // boundary versions, oldest first; v[NV-1] = V[tau]
-    typename S::Raw *out;                     // slot of the new version
-    float4 *master;                           // bf16 storage only
-    float4 *g_out;                            // nullable
+    const char *g;                  // gradient, storage type
+    const char *v[NV];              // boundary versions, oldest first; v[NV-1] = V[tau]
+    char *out;                      // slot of the new version
+    char *master;                   // fp32 master (bf16 storage only)
+    char *g_out;                    // fp32 compensated gradient, nullable
 };
 
-// Finish one vector: iterate, update, store.  x_g and x_v hold the widened inputs.
+template <typename T>
+__device__ __forceinline__ T ld_off(const char *base, uint32_t byte_off) {
+    return ld(reinterpret_cast<const T *>(base + byte_off));
+}
+template <typename T>
+__device__ __forceinline__ void st_off(char *base, uint32_t byte_off, const T &v) {
+    st(reinterpret_cast<T *>(base + byte_off), v);
+}
+
+// Finish one vector: iterate, update, store.  raw_g / raw_v hold the loaded inputs.
 template <typename S, int NV, bool COMP, bool NORMS, bool GOUT>
-__device__ __forceinline__ void finish_vector(const ChunkPtrs<S, NV> &p, uint32_t vec,
+__device__ __forceinline__ void finish_vector(const ChunkPtrs<NV> &p, uint32_t vec,
                                               const typename S::Raw &raw_g,
-                                              const typename S::Raw (&raw_v)[NV], const float4 (&m_in)[2],
+                                              const typename S::Raw (&raw_v)[NV], const v4f (&m_in)[2],
                                               float lambda, float lr, float (&acc)[3]) {
     constexpr int E = S::kElems;
     float g[E], prev[E], cur[E], first[E];
@@ -121,26 +168,26 @@ __device__ __forceinline__ void finish_vector(const ChunkPtrs<S, NV> &p, uint32_
         }
     }
     if constexpr (E == 4) {           // fp32 storage: update the newest version directly
-        float4 o;
+        v4f o;
         o.x = fmaf(-lr, g[0], prev[0]); o.y = fmaf(-lr, g[1], prev[1]);
         o.z = fmaf(-lr, g[2], prev[2]); o.w = fmaf(-lr, g[3], prev[3]);
-        p.out[vec] = o;
-        if (GOUT) p.g_out[vec] = make_float4(g[0], g[1], g[2], g[3]);
+        st_off(p.out, vec * 16u, o);
+        if (GOUT) st_off(p.g_out, vec * 16u, make_v4f(g[0], g[1], g[2], g[3]));
     } else {                          // bf16 storage: update the master, store its rounding
-        float4 m0 = m_in[0], m1 = m_in[1];
+        v4f m0 = m_in[0], m1 = m_in[1];
         m0.x = fmaf(-lr, g[0], m0.x); m0.y = fmaf(-lr, g[1], m0.y);
         m0.z = fmaf(-lr, g[2], m0.z); m0.w = fmaf(-lr, g[3], m0.w);
         m1.x = fmaf(-lr, g[4], m1.x); m1.y = fmaf(-lr, g[5], m1.y);
         m1.z = fmaf(-lr, g[6], m1.z); m1.w = fmaf(-lr, g[7], m1.w);
-        p.master[2 * (size_t)vec] = m0;
-        p.master[2 * (size_t)vec + 1] = m1;
-        uint4 o;
+        st_off(p.master, vec * 32u, m0);
+        st_off(p.master, vec * 32u + 16u, m1);
+        v4u o;
         o.x = bf16_pack(m0.x, m0.y); o.y = bf16_pack(m0.z, m0.w);
         o.z = bf16_pack(m1.x, m1.y); o.w = bf16_pack(m1.z, m1.w);
-        p.out[vec] = o;
+        st_off(p.out, vec * 16u, o);
         if (GOUT) {
-            p.g_out[2 * (size_t)vec] = make_float4(g[0], g[1], g[2], g[3]);
-            p.g_out[2 * (size_t)vec + 1] = make_float4(g[4], g[5], g[6], g[7]);
+            st_off(p.g_out, vec * 32u, make_v4f(g[0], g[1], g[2], g[3]));
+            st_off(p.g_out, vec * 32u + 16u, make_v4f(g[4], g[5], g[6], g[7]));
         }
     }
 }
@@ -151,7 +198,7 @@ __device__ __forceinline__ void finish_vector(const ChunkPtrs<S, NV> &p, uint32_
 // is also what makes the in-place case (new version written over the oldest one read) safe:
 // each vector is read and written by the same lane.
 template <typename S, int NV, bool COMP, bool NORMS, bool GOUT>
-__device__ __forceinline__ void run_chunk(const ChunkPtrs<S, NV> &p, uint32_t n_vecs, float lambda,
+__device__ __forceinline__ void run_chunk(const ChunkPtrs<NV> &p, uint32_t n_vecs, float lambda,
                                           float lr, float (&acc)[3]) {
     using Raw = typename S::Raw;
     constexpr bool kMaster = S::kElems == 8;
@@ -161,19 +208,19 @@ __device__ __forceinline__ void run_chunk(const ChunkPtrs<S, NV> &p, uint32_t n_
 
     for (uint32_t base = 0; base < n_grouped; base += group) {
         Raw rg[kUnroll], rv[kUnroll][NV];
-        float4 m[kUnroll][2];
+        v4f m[kUnroll][2];
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) rg[u] = p.g[base + u * kThreads + tid];
+        for (int u = 0; u < kUnroll; ++u) rg[u] = ld_off<Raw>(p.g, (base + u * kThreads + tid) * 16u);
 #pragma unroll
         for (int s = 0; s < NV; ++s)
 #pragma unroll
-            for (int u = 0; u < kUnroll; ++u) rv[u][s] = p.v[s][base + u * kThreads + tid];
+            for (int u = 0; u < kUnroll; ++u) rv[u][s] = ld_off<Raw>(p.v[s], (base + u * kThreads + tid) * 16u);
         if (kMaster) {
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
-                size_t vec = base + u * kThreads + tid;
-                m[u][0] = p.master[2 * vec];
-                m[u][1] = p.master[2 * vec + 1];
+                const uint32_t off = (base + u * kThreads + tid) * 32u;
+                m[u][0] = ld_off<v4f>(p.master, off);
+                m[u][1] = ld_off<v4f>(p.master, off + 16u);
             }
         }
 #pragma unroll
@@ -182,29 +229,28 @@ __device__ __forceinline__ void run_chunk(const ChunkPtrs<S, NV> &p, uint32_t n_
                                                     lr, acc);
     }
     for (uint32_t vec = n_grouped + tid; vec < n_vecs; vec += kThreads) {
-        Raw rg = p.g[vec], rv[NV];
-        float4 m[2];
+        Raw rg = ld_off<Raw>(p.g, vec * 16u), rv[NV];
+        v4f m[2];
 #pragma unroll
-        for (int s = 0; s < NV; ++s) rv[s] = p.v[s][vec];
-        if (kMaster) { m[0] = p.master[2 * (size_t)vec]; m[1] = p.master[2 * (size_t)vec + 1]; }
+        for (int s = 0; s < NV; ++s) rv[s] = ld_off<Raw>(p.v[s], vec * 16u);
+        if (kMaster) { m[0] = ld_off<v4f>(p.master, vec * 32u); m[1] = ld_off<v4f>(p.master, vec * 32u + 16u); }
         finish_vector<S, NV, COMP, NORMS, GOUT>(p, vec, rg, rv, m, lambda, lr, acc);
     }
 }
 
-// Any number of versions (K' > 4): stream them one boundary at a time.
+// Any number of versions (K' > 4): stream them one boundary at a time.  `arena` points at this
+// chunk's first element in slot 0 of the stage; slots are slot_bytes apart.
 template <typename S, bool NORMS, bool GOUT>
-__device__ __forceinline__ void run_chunk_streamed(const typename S::Raw *g_ptr, const typename S::Raw *arena,
-                                                   uint64_t slot_stride_vecs, uint32_t R, uint32_t head,
-                                                   uint32_t tau, uint32_t kp, typename S::Raw *out,
-                                                   float4 *master, float4 *g_out, uint32_t n_vecs,
-                                                   float lambda, float lr, float (&acc)[3]) {
+__device__ __forceinline__ void run_chunk_streamed(const ChunkPtrs<1> &p, const char *arena, uint64_t slot_bytes,
+                                                   uint32_t R, uint32_t head, uint32_t tau, uint32_t kp,
+                                                   uint32_t n_vecs, float lambda, float lr, float (&acc)[3]) {
     using Raw = typename S::Raw;
     constexpr int E = S::kElems;
     const uint32_t oldest = (head + R - tau) % R;
     for (uint32_t vec = threadIdx.x; vec < n_vecs; vec += kThreads) {
         float g[E], prev[E], cur[E], first[E];
-        Raw rg = g_ptr[vec];
-        Raw r0 = arena[(uint64_t)oldest * slot_stride_vecs + vec];
+        Raw rg = ld_off<Raw>(p.g, vec * 16u);
+        Raw r0 = ld_off<Raw>(arena + (uint64_t)oldest * slot_bytes, vec * 16u);
         S::widen(rg, g);
         S::widen(r0, prev);
 #pragma unroll
@@ -213,10 +259,27 @@ __device__ __forceinline__ void run_chunk_streamed(const typename S::Raw *g_ptr,
 #pragma unroll
             for (int e = 0; e < E; ++e) acc[0] = fmaf(g[e], g[e], acc[0]);
         }
-        for (uint32_t i = 1; i <= kp; ++i) {
-            uint32_t s_i = (uint32_t)(((uint64_t)i * tau) / kp);
-            uint32_t slot = (oldest + s_i) % R;
-            Raw r = arena[(uint64_t)slot * slot_stride_vecs + vec];
+        uint32_t i = 1;
+        for (; i + 3 <= kp; i += 4) {           // four boundaries at a time: their loads overlap
+            Raw r[4];
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const uint32_t s_i = (uint32_t)(((uint64_t)(i + b) * tau) / kp);
+                r[b] = ld_off<Raw>(arena + (uint64_t)((oldest + s_i) % R) * slot_bytes, vec * 16u);
+            }
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                S::widen(r[b], cur);
+#pragma unroll
+                for (int e = 0; e < E; ++e) {
+                    g[e] = approximator(g[e], lambda, cur[e], prev[e]);
+                    prev[e] = cur[e];
+                }
+            }
+        }
+        for (; i <= kp; ++i) {
+            const uint32_t s_i = (uint32_t)(((uint64_t)i * tau) / kp);
+            Raw r = ld_off<Raw>(arena + (uint64_t)((oldest + s_i) % R) * slot_bytes, vec * 16u);
             S::widen(r, cur);
 #pragma unroll
             for (int e = 0; e < E; ++e) {
@@ -233,26 +296,26 @@ __device__ __forceinline__ void run_chunk_streamed(const typename S::Raw *g_ptr,
             }
         }
         if constexpr (E == 4) {
-            float4 o;
+            v4f o;
             o.x = fmaf(-lr, g[0], prev[0]); o.y = fmaf(-lr, g[1], prev[1]);
             o.z = fmaf(-lr, g[2], prev[2]); o.w = fmaf(-lr, g[3], prev[3]);
-            out[vec] = o;
-            if (GOUT) g_out[vec] = make_float4(g[0], g[1], g[2], g[3]);
+            st_off(p.out, vec * 16u, o);
+            if (GOUT) st_off(p.g_out, vec * 16u, make_v4f(g[0], g[1], g[2], g[3]));
         } else {
-            float4 m0 = master[2 * (size_t)vec], m1 = master[2 * (size_t)vec + 1];
+            v4f m0 = ld_off<v4f>(p.master, vec * 32u), m1 = ld_off<v4f>(p.master, vec * 32u + 16u);
             m0.x = fmaf(-lr, g[0], m0.x); m0.y = fmaf(-lr, g[1], m0.y);
             m0.z = fmaf(-lr, g[2], m0.z); m0.w = fmaf(-lr, g[3], m0.w);
             m1.x = fmaf(-lr, g[4], m1.x); m1.y = fmaf(-lr, g[5], m1.y);
             m1.z = fmaf(-lr, g[6], m1.z); m1.w = fmaf(-lr, g[7], m1.w);
-            master[2 * (size_t)vec] = m0;
-            master[2 * (size_t)vec + 1] = m1;
-            uint4 o;
+            st_off(p.master, vec * 32u, m0);
+            st_off(p.master, vec * 32u + 16u, m1);
+            v4u o;
             o.x = bf16_pack(m0.x, m0.y); o.y = bf16_pack(m0.z, m0.w);
             o.z = bf16_pack(m1.x, m1.y); o.w = bf16_pack(m1.z, m1.w);
-            out[vec] = o;
+            st_off(p.out, vec * 16u, o);
             if (GOUT) {
-                g_out[2 * (size_t)vec] = make_float4(g[0], g[1], g[2], g[3]);
-                g_out[2 * (size_t)vec + 1] = make_float4(g[4], g[5], g[6], g[7]);
+                st_off(p.g_out, vec * 32u, make_v4f(g[0], g[1], g[2], g[3]));
+                st_off(p.g_out, vec * 32u + 16u, make_v4f(g[4], g[5], g[6], g[7]));
             }
         }
     }
@@ -265,127 +328,180 @@ __device__ __forceinline__ float wave_sum(float x) {
     return x;
 }
 
-// Fixed-NV dispatch target: builds the chunk's pointers from the stage entry.
+// The wave-uniform facts about one chunk, taken from its stage's table entry.
+struct ChunkInfo {
+    const char *arena;       // this chunk's first element in slot 0 of the stage's ring arena
+    uint64_t slot_bytes;     // distance between slots
+    uint64_t flat_elem0;     // this chunk's first element in slot-shaped buffers
+    uint32_t n_vecs;         // 16-byte storage vectors in the chunk
+    uint32_t R, head, tau, kp;
+};
+
+template <typename S>
+__device__ __forceinline__ ChunkInfo chunk_info(const StepArgs &a, const StageDesc &d, uint32_t chunk) {
+    constexpr uint64_t kStoreBytes = 16 / S::kElems;
+    ChunkInfo c;
+    const uint64_t e0 = (uint64_t)(chunk - uniform(d.chunk_begin)) * a.chunk_elems;
+    const uint64_t left = uniform(d.n_elems) - e0;
+    const uint32_t n_here = left < a.chunk_elems ? (uint32_t)left : a.chunk_elems;
+    c.n_vecs = n_here / S::kElems;
+    c.R = uniform((uint32_t)d.ring_depth);
+    c.head = uniform((uint32_t)d.head);
+    c.tau = uniform((uint32_t)d.tau);
+    c.kp = uniform((uint32_t)d.kp);
+    c.slot_bytes = uniform(d.slot_stride) * kStoreBytes;
+    c.arena = static_cast<const char *>(a.ring) + (uniform(d.ring_base) + e0) * kStoreBytes;
+    c.flat_elem0 = uniform(d.flat_off) + e0;
+    return c;
+}
+
+// Fixed-NV dispatch target: builds the chunk's pointers.
 template <typename S, int NV, bool COMP, bool NORMS, bool GOUT>
-__device__ __forceinline__ void do_chunk(const StepArgs &a, const typename S::Raw *arena, uint64_t stride_vecs,
-                                         uint64_t flat_vec0, uint32_t R, uint32_t head, uint32_t tau,
-                                         uint32_t n_vecs, float (&acc)[3]) {
-    using Raw = typename S::Raw;
-    ChunkPtrs<S, NV> p;
-    p.g = reinterpret_cast<const Raw *>(a.grads) + flat_vec0;
-    const uint32_t oldest = (head + R - tau) % R;
+__device__ __forceinline__ void do_chunk(const StepArgs &a, const ChunkInfo &c, float (&acc)[3]) {
+    constexpr uint64_t kStoreBytes = 16 / S::kElems;
+    ChunkPtrs<NV> p;
+    p.g = static_cast<const char *>(a.grads) + c.flat_elem0 * kStoreBytes;
+    const uint32_t oldest = (c.head + c.R - c.tau) % c.R;
     constexpr uint32_t kp = NV - 1;
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
         // NV == 1: only V[tau].  Otherwise boundary s_i = floor(i*tau/K') of the K' = NV-1 segments.
-        uint32_t s_i = NV == 1 ? tau : (uint32_t)(((uint64_t)i * tau) / (kp ? kp : 1));
-        p.v[i] = arena + (uint64_t)((oldest + s_i) % R) * stride_vecs;
+        const uint32_t s_i = NV == 1 ? c.tau : (uint32_t)(((uint64_t)i * c.tau) / (kp ? kp : 1));
+        p.v[i] = c.arena + (uint64_t)((oldest + s_i) % c.R) * c.slot_bytes;
     }
-    p.out = const_cast<Raw *>(arena) + (uint64_t)((head + 1) % R) * stride_vecs;
-    constexpr uint64_t f4_per_vec = S::kElems / 4;
-    p.master = a.master ? reinterpret_cast<float4 *>(a.master) + flat_vec0 * f4_per_vec : nullptr;
-    p.g_out = GOUT ? reinterpret_cast<float4 *>(a.grad_out) + flat_vec0 * f4_per_vec : nullptr;
-    run_chunk<S, NV, COMP, NORMS, GOUT>(p, n_vecs, a.lambda, a.lr, acc);
+    p.out = const_cast<char *>(c.arena) + (uint64_t)((c.head + 1) % c.R) * c.slot_bytes;
+    p.master = a.master ? reinterpret_cast<char *>(a.master) + c.flat_elem0 * 4 : nullptr;
+    p.g_out = GOUT ? reinterpret_cast<char *>(a.grad_out) + c.flat_elem0 * 4 : nullptr;
+    run_chunk<S, NV, COMP, NORMS, GOUT>(p, c.n_vecs, a.lambda, a.lr, acc);
+}
+
+// One chunk, whatever its K': picks the unrolled variant (K' <= 4 or <= 8) or the streamed one, then
+// reduces the three partial sums of the workgroup and writes the chunk's partial.
+template <typename S, int LEVEL, bool NORMS, bool GOUT>
+__device__ __forceinline__ void process_chunk(const StepArgs &a, const ChunkInfo &c, uint32_t chunk,
+                                              float (&red)[3][kWaves]) {
+    float acc[3] = {0.f, 0.f, 0.f};
+    // versions to read: the K'+1 boundaries; with K' = 0 only V[tau], plus V[0] when the weight
+    // gap is wanted for the norms
+    if (c.kp == 0) {
+        if (NORMS && c.tau > 0) do_chunk<S, 2, false, NORMS, GOUT>(a, c, acc);
+        else do_chunk<S, 1, false, NORMS, GOUT>(a, c, acc);
+    } else if (c.kp == 1) {
+        do_chunk<S, 2, true, NORMS, GOUT>(a, c, acc);
+    } else if (c.kp == 2) {
+        do_chunk<S, 3, true, NORMS, GOUT>(a, c, acc);
+    } else if (c.kp == 3) {
+        do_chunk<S, 4, true, NORMS, GOUT>(a, c, acc);
+    } else if (c.kp == 4) {
+        do_chunk<S, 5, true, NORMS, GOUT>(a, c, acc);
+    } else if (LEVEL >= 1 && c.kp == 5) {
+        do_chunk<S, 6, true, NORMS, GOUT>(a, c, acc);
+    } else if (LEVEL >= 1 && c.kp == 6) {
+        do_chunk<S, 7, true, NORMS, GOUT>(a, c, acc);
+    } else if (LEVEL >= 1 && c.kp == 7) {
+        do_chunk<S, 8, true, NORMS, GOUT>(a, c, acc);
+    } else if (LEVEL >= 1 && c.kp == 8) {
+        do_chunk<S, 9, true, NORMS, GOUT>(a, c, acc);
+    } else if (LEVEL >= 2) {
+        constexpr uint64_t kStoreBytes = 16 / S::kElems;
+        ChunkPtrs<1> p;
+        p.g = static_cast<const char *>(a.grads) + c.flat_elem0 * kStoreBytes;
+        p.v[0] = nullptr;
+        p.out = const_cast<char *>(c.arena) + (uint64_t)((c.head + 1) % c.R) * c.slot_bytes;
+        p.master = a.master ? reinterpret_cast<char *>(a.master) + c.flat_elem0 * 4 : nullptr;
+        p.g_out = GOUT ? reinterpret_cast<char *>(a.grad_out) + c.flat_elem0 * 4 : nullptr;
+        run_chunk_streamed<S, NORMS, GOUT>(p, c.arena, c.slot_bytes, c.R, c.head, c.tau, c.kp, c.n_vecs,
+                                           a.lambda, a.lr, acc);
+    }
+    if (NORMS) {
+        const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+#pragma unroll
+        for (int k = 0; k < 3; ++k) {
+            float s = wave_sum(acc[k]);
+            if (lane == 0) red[k][wave] = s;
+        }
+        __syncthreads();
+        if (threadIdx.x < 3) {
+            float s = 0.f;
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) s += red[threadIdx.x][w];
+            a.partials[(size_t)threadIdx.x * a.n_chunks + chunk] = s;     // three series, each contiguous
+        }
+    }
 }
 
 // ---- the step kernel ----------------------------------------------------------------------------
-// STREAMED = false: every stage has K' <= 4 (the common case); the generic path is not even
-// compiled in, which keeps the register footprint small.
-template <typename S, bool STREAMED, bool NORMS, bool GOUT>
+// PERSISTENT = true : a fixed grid strides over the chunks; the stage table is staged in LDS once
+//                     per workgroup and each chunk's stage is looked up there.
+// PERSISTENT = false: one workgroup per chunk, scheduled by the hardware dispatcher; the table is
+//                     read straight from the kernel-argument segment with scalar loads (the
+//                     block index is uniform, so nothing needs LDS or a barrier).
+// LEVEL 0 / 1 / 2   : largest K' of any stage is <= 4 / <= 8 / anything; paths a launch cannot
+//                     need are not compiled in, which keeps the register footprint small.
+template <typename S, bool PERSISTENT, int LEVEL, bool NORMS, bool GOUT>
 __global__ void __launch_bounds__(kThreads) step_kernel(const StepArgs a) {
-    using Raw = typename S::Raw;
-    __shared__ StageDesc tab[FERRET_MAX_STAGES];
     __shared__ float red[3][kWaves];
-
-    {   // stage table: kernel-argument segment -> LDS, 12 dwords per stage
-        const uint32_t *src = reinterpret_cast<const uint32_t *>(a.stage);
-        uint32_t *dst = reinterpret_cast<uint32_t *>(tab);
-        const uint32_t n_words = a.n_stages * (sizeof(StageDesc) / 4);
-        for (uint32_t i = threadIdx.x; i < n_words; i += kThreads) dst[i] = src[i];
-    }
-    __syncthreads();
-
-    uint32_t stage = 0;
-    for (uint32_t chunk = blockIdx.x; chunk < a.n_chunks; chunk += gridDim.x) {
-        while (stage + 1 < a.n_stages && chunk >= tab[stage + 1].chunk_begin) ++stage;
-        stage = uniform(stage);
-        const StageDesc &d = tab[stage];
-        const uint64_t e0 = (uint64_t)(chunk - uniform(d.chunk_begin)) * a.chunk_elems;
-        const uint64_t n_stage = uniform(d.n_elems);
-        const uint64_t left = n_stage - e0;
-        const uint32_t n_here = left < a.chunk_elems ? (uint32_t)left : a.chunk_elems;
-        const uint32_t n_vecs = n_here / S::kElems;
-        const uint32_t R = uniform((uint32_t)d.ring_depth), head = uniform((uint32_t)d.head);
-        const uint32_t tau = uniform((uint32_t)d.tau), kp = uniform((uint32_t)d.kp);
-        const uint64_t stride_vecs = uniform(d.slot_stride) / S::kElems;
-        const Raw *arena = reinterpret_cast<const Raw *>(a.ring) + (uniform(d.ring_base) + e0) / S::kElems;
-        const uint64_t flat_vec0 = (uniform(d.flat_off) + e0) / S::kElems;
-
-        float acc[3] = {0.f, 0.f, 0.f};
-        // versions to read: the K'+1 boundaries; with K' = 0 only V[tau], plus V[0] when the
-        // weight gap is wanted for the norms
-        if (kp == 0) {
-            if (NORMS && tau > 0)
-                do_chunk<S, 2, false, NORMS, GOUT>(a, arena, stride_vecs, flat_vec0, R, head, tau, n_vecs, acc);
-            else
-                do_chunk<S, 1, false, NORMS, GOUT>(a, arena, stride_vecs, flat_vec0, R, head, tau, n_vecs, acc);
-        } else if (kp == 1) {
-            do_chunk<S, 2, true, NORMS, GOUT>(a, arena, stride_vecs, flat_vec0, R, head, tau, n_vecs, acc);
-        } else if (kp == 2) {
-            do_chunk<S, 3, true, NORMS, GOUT>(a, arena, stride_vecs, flat_vec0, R, head, tau, n_vecs, acc);
-        } else if (kp == 3) {
-            do_chunk<S, 4, true, NORMS, GOUT>(a, arena, stride_vecs, flat_vec0, R, head, tau, n_vecs, acc);
-        } else if (kp == 4) {
-            do_chunk<S, 5, true, NORMS, GOUT>(a, arena, stride_vecs, flat_vec0, R, head, tau, n_vecs, acc);
-        } else if (STREAMED) {
-            constexpr uint64_t f4_per_vec = S::kElems / 4;
-            run_chunk_streamed<S, NORMS, GOUT>(
-                reinterpret_cast<const Raw *>(a.grads) + flat_vec0, arena, stride_vecs, R, head, tau, kp,
-                const_cast<Raw *>(arena) + (uint64_t)((head + 1) % R) * stride_vecs,
-                a.master ? reinterpret_cast<float4 *>(a.master) + flat_vec0 * f4_per_vec : nullptr,
-                GOUT ? reinterpret_cast<float4 *>(a.grad_out) + flat_vec0 * f4_per_vec : nullptr, n_vecs,
-                a.lambda, a.lr, acc);
+    if constexpr (PERSISTENT) {
+        __shared__ StageDesc tab[FERRET_MAX_STAGES];
+        {   // stage table: kernel-argument segment -> LDS, 12 dwords per stage
+            const uint32_t *src = reinterpret_cast<const uint32_t *>(a.stage);
+            uint32_t *dst = reinterpret_cast<uint32_t *>(tab);
+            const uint32_t n_words = a.n_stages * (sizeof(StageDesc) / 4);
+            for (uint32_t i = threadIdx.x; i < n_words; i += kThreads) dst[i] = src[i];
         }
-
-        if (NORMS) {
-            const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
-#pragma unroll
-            for (int k = 0; k < 3; ++k) {
-                float s = wave_sum(acc[k]);
-                if (lane == 0) red[k][wave] = s;
-            }
-            __syncthreads();
-            if (threadIdx.x < 3) {
-                float s = 0.f;
-#pragma unroll
-                for (int w = 0; w < kWaves; ++w) s += red[threadIdx.x][w];
-                a.partials[(size_t)chunk * 3 + threadIdx.x] = s;
-            }
-            __syncthreads();
+        __syncthreads();
+        uint32_t stage = 0;
+        for (uint32_t chunk = blockIdx.x; chunk < a.n_chunks; chunk += gridDim.x) {
+            while (stage + 1 < a.n_stages && chunk >= tab[stage + 1].chunk_begin) ++stage;
+            stage = uniform(stage);
+            const ChunkInfo c = chunk_info<S>(a, tab[stage], chunk);
+            process_chunk<S, LEVEL, NORMS, GOUT>(a, c, chunk, red);
+            if (NORMS) __syncthreads();     // red[] is reused by the next chunk
         }
+    } else {
+        const uint32_t chunk = blockIdx.x;
+        // stage = number of stages (beyond the first) that begin at or before this chunk;
+        // unused table entries hold UINT32_MAX and never count
+        uint32_t stage = 0;
+#pragma unroll
+        for (uint32_t j = 1; j < 16; ++j) stage += chunk >= a.chunk_begin[j] ? 1u : 0u;
+        if (a.n_stages > 16) {
+#pragma unroll
+            for (uint32_t j = 16; j < FERRET_MAX_STAGES; ++j) stage += chunk >= a.chunk_begin[j] ? 1u : 0u;
+        }
+        const ChunkInfo c = chunk_info<S>(a, a.stage[stage], chunk);
+        process_chunk<S, LEVEL, NORMS, GOUT>(a, c, chunk, red);
     }
 }
 
-// Sum the per-chunk partials of each stage in chunk order, in fp64.  One workgroup per stage.
-__global__ void __launch_bounds__(kThreads) norms_finalize_kernel(const StepArgs a, float *norms_out) {
-    __shared__ double red[3][kThreads];
-    const uint32_t j = blockIdx.x;
+// Sum the per-chunk partials of each stage in a fixed order, in fp64.  Grid = (stage, series):
+// one workgroup adds up one of the three series of one stage.  Lane t takes chunks t, t+1024, ...
+// (all loads independent), then the 1024 lane sums are combined by a fixed shuffle tree and a
+// fixed order across wavefronts, so the result does not depend on how the step kernel was launched.
+constexpr int kFinalizeThreads = 1024;
+__global__ void __launch_bounds__(kFinalizeThreads) norms_finalize_kernel(const StepArgs a, float *norms_out) {
+    __shared__ double red[kFinalizeThreads / 64];
+    const uint32_t j = blockIdx.x, k = blockIdx.y;
     const uint32_t c0 = a.stage[j].chunk_begin;
     const uint32_t c1 = j + 1 < a.n_stages ? a.stage[j + 1].chunk_begin : a.n_chunks;
-    double s[3] = {0.0, 0.0, 0.0};
-    for (uint32_t c = c0 + threadIdx.x; c < c1; c += kThreads) {
-        s[0] += (double)a.partials[(size_t)c * 3 + 0];
-        s[1] += (double)a.partials[(size_t)c * 3 + 1];
-        s[2] += (double)a.partials[(size_t)c * 3 + 2];
+    const float *series = a.partials + (size_t)k * a.n_chunks;
+    double s = 0.0;
+    uint32_t c = c0 + threadIdx.x;
+    for (; c + 3 * kFinalizeThreads < c1; c += 4 * kFinalizeThreads) {
+        const float x0 = series[c], x1 = series[c + kFinalizeThreads], x2 = series[c + 2 * kFinalizeThreads],
+                    x3 = series[c + 3 * kFinalizeThreads];
+        s += (double)x0; s += (double)x1; s += (double)x2; s += (double)x3;
     }
-    for (int k = 0; k < 3; ++k) red[k][threadIdx.x] = s[k];
+    for (; c < c1; c += kFinalizeThreads) s += (double)series[c];
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off, 64);
+    if ((threadIdx.x & 63u) == 0) red[threadIdx.x >> 6] = s;
     __syncthreads();
-    for (int width = kThreads / 2; width >= 1; width >>= 1) {
-        if ((int)threadIdx.x < width)
-            for (int k = 0; k < 3; ++k) red[k][threadIdx.x] += red[k][threadIdx.x + width];
-        __syncthreads();
+    if (threadIdx.x == 0) {
+        double total = 0.0;
+        for (int w = 0; w < kFinalizeThreads / 64; ++w) total += red[w];
+        norms_out[j * 3 + k] = (float)total;
     }
-    if (threadIdx.x < 3) norms_out[j * 3 + threadIdx.x] = (float)red[threadIdx.x][0];
 }
 
 // ---- push: fp32 source -> ring slot (+ master) ----------------------------------------------------
@@ -428,15 +544,17 @@ __global__ void __launch_bounds__(kThreads) push_kernel(const PushArgs a) {
     }
 }
 
-__global__ void __launch_bounds__(kThreads) copy_kernel(uint4 *dst, const uint4 *src, size_t n_vecs) {
-    const size_t stride = (size_t)gridDim.x * kThreads * kUnroll;
-    size_t i = (size_t)blockIdx.x * kThreads * kUnroll + threadIdx.x;
-    for (; i + kThreads < n_vecs; i += stride) {
-        uint4 x = src[i], y = src[i + kThreads];
-        dst[i] = x;
-        dst[i + kThreads] = y;
-    }
-    if (i < n_vecs) dst[i] = src[i];
+// Plain streaming copy: one workgroup per 16 KiB, four 16-byte vectors per lane, loads before stores.
+constexpr int kCopyVecsPerLane = 4;
+__global__ void __launch_bounds__(kThreads) copy_kernel(v4u *dst, const v4u *src, size_t n_vecs) {
+    const size_t base = (size_t)blockIdx.x * kThreads * kCopyVecsPerLane + threadIdx.x;
+    v4u x[kCopyVecsPerLane];
+#pragma unroll
+    for (int u = 0; u < kCopyVecsPerLane; ++u)
+        if (base + (size_t)u * kThreads < n_vecs) x[u] = ld(&src[base + (size_t)u * kThreads]);
+#pragma unroll
+    for (int u = 0; u < kCopyVecsPerLane; ++u)
+        if (base + (size_t)u * kThreads < n_vecs) st(&dst[base + (size_t)u * kThreads], x[u]);
 }
 
 // ---- per-launch event timing of the step kernel ---------------------------------------------------
@@ -497,28 +615,57 @@ static int cu_count(int *err) {
 
 static uint32_t grid_for(const ferret_plan &plan, uint32_t n_chunks, int *err) {
     int bpc = plan.blocks_per_cu;
-    if (bpc < 0) return n_chunks;                 // one workgroup per chunk
-    if (bpc == 0) bpc = 8;
+    if (bpc <= 0) return n_chunks;                // default: one workgroup per chunk
     int cus = cu_count(err);
     if (*err) return 0;
     uint64_t g = (uint64_t)cus * (uint64_t)bpc;
     return g < n_chunks ? (uint32_t)g : n_chunks;
 }
 
-template <typename S>
-static hipError_t launch_step_typed(const StepArgs &a, bool streamed, bool norms, bool gout, uint32_t grid,
-                                    hipStream_t st) {
-#define FERRET_LAUNCH(ST, NO, GO) \
-    hipLaunchKernelGGL((step_kernel<S, ST, NO, GO>), dim3(grid), dim3(kThreads), 0, st, a)
-    if (streamed) {
-        if (norms) { if (gout) FERRET_LAUNCH(true, true, true); else FERRET_LAUNCH(true, true, false); }
-        else       { if (gout) FERRET_LAUNCH(true, false, true); else FERRET_LAUNCH(true, false, false); }
-    } else {
-        if (norms) { if (gout) FERRET_LAUNCH(false, true, true); else FERRET_LAUNCH(false, true, false); }
-        else       { if (gout) FERRET_LAUNCH(false, false, true); else FERRET_LAUNCH(false, false, false); }
+// Resident-workgroup cap.  Measured on MI355X: this read-mostly mix of 6-7 streams peaks when a CU
+// holds roughly 100 KB of requests in flight and loses a few per cent beyond that, so the launch
+// reserves LDS the kernel never touches: with 160 KiB of LDS per CU, asking for
+// floor(160 KiB / cap) bytes per workgroup lets exactly `cap` of them be resident.
+constexpr uint32_t kLdsPerCu = 160u * 1024u;
+constexpr uint32_t kLdsPerBlockMax = 64u * 1024u;
+
+static uint32_t reserve_lds_for_cap(const ferret_plan &plan, const StepArgs &a, bool persistent) {
+    int32_t cap = plan.resident_cap;
+    if (cap == 0) {
+        // default: cap only steps whose traffic is far beyond the 256 MB memory-side cache; steps
+        // that run out of that cache are latency-bound instead and want every wave they can get
+        const uint64_t sb = plan.prec == FERRET_F32 ? 4 : 2;
+        uint64_t bytes = 0;
+        for (uint32_t j = 0; j < a.n_stages; ++j)
+            bytes += a.stage[j].n_elems * (sb * (a.stage[j].kp + 3u) + (plan.prec == FERRET_F32 ? 0u : 8u));
+        cap = bytes > kCapThresholdBytes ? (plan.prec == FERRET_F32 ? kDefaultResidentCapF32 : kDefaultResidentCapBf16)
+                                         : -1;
     }
+    if (cap <= 0) return 0;
+    const uint32_t used = (persistent ? (uint32_t)sizeof(StageDesc) * FERRET_MAX_STAGES : 0u) + 64u;
+    uint32_t want = kLdsPerCu / (uint32_t)cap;
+    want = want / 512u * 512u;                          // LDS is granted in 512-byte granules
+    if (want > kLdsPerBlockMax) want = kLdsPerBlockMax;
+    return want > used + 512u ? want - used - 512u : 0u;
+}
+
+template <typename S, bool PERSISTENT, int LEVEL>
+static hipError_t launch_step_level(const StepArgs &a, bool norms, bool gout, uint32_t grid, uint32_t dyn_lds,
+                                    hipStream_t st) {
+#define FERRET_LAUNCH(NO, GO) \
+    hipLaunchKernelGGL((step_kernel<S, PERSISTENT, LEVEL, NO, GO>), dim3(grid), dim3(kThreads), dyn_lds, st, a)
+    if (norms) { if (gout) FERRET_LAUNCH(true, true); else FERRET_LAUNCH(true, false); }
+    else       { if (gout) FERRET_LAUNCH(false, true); else FERRET_LAUNCH(false, false); }
 #undef FERRET_LAUNCH
     return hipGetLastError();
+}
+
+template <typename S, bool PERSISTENT>
+static hipError_t launch_step_typed(const StepArgs &a, int level, bool norms, bool gout, uint32_t grid,
+                                    uint32_t dyn_lds, hipStream_t st) {
+    if (level == 0) return launch_step_level<S, PERSISTENT, 0>(a, norms, gout, grid, dyn_lds, st);
+    if (level == 1) return launch_step_level<S, PERSISTENT, 1>(a, norms, gout, grid, dyn_lds, st);
+    return launch_step_level<S, PERSISTENT, 2>(a, norms, gout, grid, dyn_lds, st);
 }
 
 int launch_step(const ferret_plan &plan, const StepArgs &a, float *norms_out, void *stream) {
@@ -527,17 +674,27 @@ int launch_step(const ferret_plan &plan, const StepArgs &a, float *norms_out, vo
     const uint32_t grid = grid_for(plan, a.n_chunks, &err);
     if (err) return err;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    bool streamed = false;
-    for (uint32_t j = 0; j < a.n_stages; ++j) streamed |= a.stage[j].kp + 1 > kMaxUnrolledVersions;
+    int streamed = 0;    // kernel level: which K' the launch has to cover
+    for (uint32_t j = 0; j < a.n_stages; ++j) {
+        const int need = a.stage[j].kp <= kUnrolledItersSmall ? 0 : (a.stage[j].kp <= kUnrolledItersMid ? 1 : 2);
+        streamed = need > streamed ? need : streamed;
+    }
     const bool norms = norms_out != nullptr, gout = a.grad_out != nullptr;
     const bool timed = g_prof.on && g_prof.used < (int32_t)g_prof.start.size();
     if (timed) (void)hipEventRecord(g_prof.start[g_prof.used], st);
-    hipError_t e = plan.prec == FERRET_F32 ? launch_step_typed<F32Store>(a, streamed, norms, gout, grid, st)
-                                           : launch_step_typed<Bf16Store>(a, streamed, norms, gout, grid, st);
+    const bool persistent = grid < a.n_chunks;
+    const uint32_t lds = reserve_lds_for_cap(plan, a, persistent);
+    hipError_t e;
+    if (plan.prec == FERRET_F32)
+        e = persistent ? launch_step_typed<F32Store, true>(a, streamed, norms, gout, grid, lds, st)
+                       : launch_step_typed<F32Store, false>(a, streamed, norms, gout, grid, lds, st);
+    else
+        e = persistent ? launch_step_typed<Bf16Store, true>(a, streamed, norms, gout, grid, lds, st)
+                       : launch_step_typed<Bf16Store, false>(a, streamed, norms, gout, grid, lds, st);
     if (timed) (void)hipEventRecord(g_prof.stop[g_prof.used++], st);
     if (e != hipSuccess) return (int)e;
     if (norms) {
-        hipLaunchKernelGGL(norms_finalize_kernel, dim3(a.n_stages), dim3(kThreads), 0, st, a, norms_out);
+        hipLaunchKernelGGL(norms_finalize_kernel, dim3(a.n_stages, 3), dim3(kFinalizeThreads), 0, st, a, norms_out);
         e = hipGetLastError();
     }
     return (int)e;
@@ -557,15 +714,12 @@ int launch_push(const ferret_plan &plan, const PushArgs &a, void *stream) {
 }
 
 int launch_copy(void *dst, const void *src, size_t n_bytes, void *stream) {
-    int err = 0;
-    int cus = cu_count(&err);
-    if (err) return err;
     const size_t n_vecs = n_bytes / 16;
-    size_t want = (n_vecs + kThreads * kUnroll - 1) / (kThreads * kUnroll);
-    size_t cap = (size_t)cus * 8;
-    uint32_t grid = (uint32_t)(want < cap ? want : cap);
-    hipLaunchKernelGGL(copy_kernel, dim3(grid), dim3(kThreads), 0, static_cast<hipStream_t>(stream),
-                       static_cast<uint4 *>(dst), static_cast<const uint4 *>(src), n_vecs);
+    const size_t per_block = (size_t)kThreads * kCopyVecsPerLane;
+    const size_t blocks = (n_vecs + per_block - 1) / per_block;
+    if (blocks > 0x7fffffffull) return (int)hipErrorInvalidValue;
+    hipLaunchKernelGGL(copy_kernel, dim3((uint32_t)blocks), dim3(kThreads), 0, static_cast<hipStream_t>(stream),
+                       static_cast<v4u *>(dst), static_cast<const v4u *>(src), n_vecs);
     return (int)hipGetLastError();
 }
 

@@ -73,7 +73,7 @@ RAGGED = [
 
 @pytest.mark.parametrize("name,sizes,tau,R,K", RAGGED)
 @pytest.mark.parametrize("precision", ["f32", "bf16"])
-@pytest.mark.parametrize("chunk_units", [1, 0])
+@pytest.mark.parametrize("chunk_units", [0, 3, 8])
 def test_ragged_shapes(name, sizes, tau, R, K, precision, chunk_units):
     unit = 1024 if precision == "f32" else 2048
     w = W.custom_workload(name, sizes, tau, R, K, precision=precision, seed=7)
@@ -195,7 +195,8 @@ def test_outputs_do_not_depend_on_optional_outputs_or_grid():
     results = []
     for tuning, norms, gout in [(None, True, True), (dict(blocks_per_cu=-1), True, True),
                                 (dict(blocks_per_cu=1), False, False), (dict(blocks_per_cu=3), True, False),
-                                (dict(slot_align_elems=4096, slot_skew_elems=520), False, True)]:
+                                (dict(slot_align_elems=4096, slot_skew_elems=520), False, True),
+                                (dict(resident_cap=3), True, True), (dict(resident_cap=-1, blocks_per_cu=2), True, True)]:
         plan, st, host = PU.load_workload(w, amplified=True, tuning=tuning)
         st.step(w.lam, w.lr, norms=norms, grad_out=gout)
         torch.cuda.synchronize()

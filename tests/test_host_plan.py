@@ -186,7 +186,7 @@ BAD_PLANS = [
     dict(tensors=[(10, 0)], n_stages=1, tau=[0], chunk=1000),
     dict(tensors=[(10, 0)], n_stages=1, tau=[0], tuning=dict(slot_align_elems=100)),
     dict(tensors=[(10, 0)], n_stages=1, tau=[0], tuning=dict(slot_skew_elems=3)),
-    dict(tensors=[(10, 0)], n_stages=1, tau=[0], tuning=dict(reserved=1)),
+    dict(tensors=[(10, 0)], n_stages=1, tau=[0], tuning=dict(resident_cap=33)),
 ]
 
 
