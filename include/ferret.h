@@ -101,7 +101,7 @@ typedef struct ferret_plan ferret_plan;   /* opaque; host memory; owned by the c
  *                       maximum staleness of stage j in a P-stage pipeline is P-1-j
  *   n_iters             K >= 0, or FERRET_ITERS_FULL
  *   ring_depth          R >= 1 versions kept per stage, or FERRET_RING_DEPTH_MINIMAL
- *   chunk_elems         0 = default; otherwise a multiple of 1024 (fp32) / 2048 (bf16)
+ *   chunk_elems         0 = default (1024 fp32 / 2048 bf16); otherwise a multiple of 1024, at most 2^24
  *   tuning              NULL or options
  *   out_plan            receives the plan; heads start at slot 0 with no valid version
  */

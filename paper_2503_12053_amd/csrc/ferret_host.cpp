@@ -28,7 +28,7 @@ void set_error(const char *fmt, ...) {
 
 static inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 
-static inline int64_t vec_elems(ferret_precision p) { return p == FERRET_F32 ? 4 : 8; }
+static inline int64_t vec_elems(ferret_precision p) { return p == FERRET_F32 ? 4 : FERRET_BF16_LANE_ELEMS; }
 static inline int64_t storage_bytes(ferret_precision p) { return p == FERRET_F32 ? 4 : 2; }
 
 constexpr int64_t kThreads = 256;          // workgroup size of every kernel
@@ -92,7 +92,8 @@ ferret_status ferret_plan_buckets_tuned(const ferret_tensor *tensors, int32_t n_
     }
     const int64_t vec = vec_elems(prec);
     const int64_t chunk_unit = kThreads * vec;                 // one vector per thread
-    if (chunk_elems == 0) chunk_elems = chunk_unit;          // one 16-byte vector per lane per stream (measured best)
+    // default (measured best): fp32 one 16-byte vector per lane per stream, bf16 two 8-byte vectors
+    if (chunk_elems == 0) chunk_elems = prec == FERRET_F32 ? chunk_unit : 2 * chunk_unit;
     if (chunk_elems < 0 || chunk_elems % chunk_unit != 0 || chunk_elems > (int64_t(1) << 24)) {   // lanes address a chunk with 32-bit byte offsets
         set_error("plan: chunk_elems = %lld, need a positive multiple of %lld up to 2^24", (long long)chunk_elems,
                   (long long)chunk_unit);

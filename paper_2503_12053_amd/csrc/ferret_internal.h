@@ -8,6 +8,13 @@
 
 #include "ferret.h"
 
+// Elements of bf16 storage one lane handles per vector (4 or 8); fp32 storage always 4.
+// Measured on MI355X: 4 (8-byte loads, every wavefront access one contiguous run, master as one
+// float4 per lane) beats 8 (16-byte loads but the master split in two half-line accesses) by ~4 %.
+#ifndef FERRET_BF16_LANE_ELEMS
+#define FERRET_BF16_LANE_ELEMS 4
+#endif
+
 namespace ferret {
 
 // ---- what travels to the device as a kernel argument -------------------------------------

@@ -46,11 +46,12 @@ constexpr int kUnrolledItersSmall = 4;    // LEVEL 0 kernels: every stage has K'
 constexpr int kUnrolledItersMid = 8;      // LEVEL 1 kernels: K' <= 8; LEVEL 2 adds the streamed path for any K'
 constexpr int kDefaultResidentCapF32 = 4;   // workgroups per CU, see reserve_lds_for_cap
 constexpr int kDefaultResidentCapBf16 = 3;
-constexpr uint64_t kCapThresholdBytes = 512ull << 20;   // K' <= 4 runs fully unrolled
+constexpr uint64_t kCapThresholdBytes = 512ull << 20;
 
 // 16-byte vectors as clang vector types (so that the non-temporal builtins accept them)
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+typedef uint32_t v2u __attribute__((ext_vector_type(2)));
 
 // ---- small device helpers ---------------------------------------------------------------------
 template <typename T>
@@ -91,22 +92,52 @@ __device__ __forceinline__ uint32_t bf16_rne(float f) {
 }
 __device__ __forceinline__ uint32_t bf16_pack(float lo, float hi) { return bf16_rne(lo) | (bf16_rne(hi) << 16); }
 
-// One 16-byte vector of the storage type, widened to fp32 lanes.
+// Storage traits: the lane-vector of the ring / gradient storage type.
+//   kElems      elements one lane handles per vector        kStoreBytes  bytes per stored element
+//   Raw         register type of one load of that vector    kRawBytes    bytes of that vector
+//   kMaster     the update goes to an fp32 master copy (kF4 = kElems/4 float4s per lane-vector)
 struct F32Store {
     using Raw = v4f;
-    static constexpr int kElems = 4;
+    static constexpr int kElems = 4, kStoreBytes = 4, kRawBytes = 16, kF4 = 1;
+    static constexpr bool kMaster = false;
     __device__ static __forceinline__ void widen(const Raw &r, float (&x)[kElems]) {
         x[0] = r.x; x[1] = r.y; x[2] = r.z; x[3] = r.w;
     }
+    __device__ static __forceinline__ Raw narrow(const float (&x)[kElems]) { return make_v4f(x[0], x[1], x[2], x[3]); }
 };
-struct Bf16Store {
+struct Bf16Store8 {      // eight bf16 (16 bytes) per lane: widest loads, master as two float4 32 bytes apart
     using Raw = v4u;
-    static constexpr int kElems = 8;
+    static constexpr int kElems = 8, kStoreBytes = 2, kRawBytes = 16, kF4 = 2;
+    static constexpr bool kMaster = true;
     __device__ static __forceinline__ void widen(const Raw &r, float (&x)[kElems]) {
         x[0] = bf16_lo(r.x); x[1] = bf16_hi(r.x); x[2] = bf16_lo(r.y); x[3] = bf16_hi(r.y);
         x[4] = bf16_lo(r.z); x[5] = bf16_hi(r.z); x[6] = bf16_lo(r.w); x[7] = bf16_hi(r.w);
     }
+    __device__ static __forceinline__ Raw narrow(const float (&x)[kElems]) {
+        Raw o;
+        o.x = bf16_pack(x[0], x[1]); o.y = bf16_pack(x[2], x[3]);
+        o.z = bf16_pack(x[4], x[5]); o.w = bf16_pack(x[6], x[7]);
+        return o;
+    }
 };
+struct Bf16Store4 {      // four bf16 (8 bytes) per lane: every access of a wavefront is one contiguous run
+    using Raw = v2u;
+    static constexpr int kElems = 4, kStoreBytes = 2, kRawBytes = 8, kF4 = 1;
+    static constexpr bool kMaster = true;
+    __device__ static __forceinline__ void widen(const Raw &r, float (&x)[kElems]) {
+        x[0] = bf16_lo(r.x); x[1] = bf16_hi(r.x); x[2] = bf16_lo(r.y); x[3] = bf16_hi(r.y);
+    }
+    __device__ static __forceinline__ Raw narrow(const float (&x)[kElems]) {
+        Raw o;
+        o.x = bf16_pack(x[0], x[1]); o.y = bf16_pack(x[2], x[3]);
+        return o;
+    }
+};
+#if FERRET_BF16_LANE_ELEMS == 8
+using Bf16Store = Bf16Store8;
+#else
+using Bf16Store = Bf16Store4;
+#endif
 
 // A_I applied in place: g <- g + lambda * g * g * (v_new - v_old)
 __device__ __forceinline__ float approximator(float g, float lambda, float v_new, float v_old) {
@@ -134,11 +165,47 @@ __device__ __forceinline__ void st_off(char *base, uint32_t byte_off, const T &v
     st(reinterpret_cast<T *>(base + byte_off), v);
 }
 
+template <typename S>
+__device__ __forceinline__ void load_master(const char *master, uint32_t vec, v4f (&m)[S::kF4]) {
+    if (S::kMaster) {
+#pragma unroll
+        for (int q = 0; q < S::kF4; ++q) m[q] = ld_off<v4f>(master, vec * (uint32_t)(S::kElems * 4) + 16u * q);
+    }
+}
+
+// theta_next = V[tau] - eta * g (fp32 storage), or master - eta * g with the stored version its
+// round-to-nearest-even bf16; then the stores of one lane-vector.
+template <typename S, int NV, bool GOUT>
+__device__ __forceinline__ void update_and_store(const ChunkPtrs<NV> &p, uint32_t vec, const float (&g)[S::kElems],
+                                                 const float (&newest)[S::kElems], const v4f (&m_in)[S::kF4],
+                                                 float lr) {
+    constexpr int E = S::kElems;
+    constexpr uint32_t kF32Bytes = E * 4;
+    float w[E];
+    if (S::kMaster) {
+#pragma unroll
+        for (int q = 0; q < S::kF4; ++q) {
+            w[4 * q + 0] = fmaf(-lr, g[4 * q + 0], m_in[q].x); w[4 * q + 1] = fmaf(-lr, g[4 * q + 1], m_in[q].y);
+            w[4 * q + 2] = fmaf(-lr, g[4 * q + 2], m_in[q].z); w[4 * q + 3] = fmaf(-lr, g[4 * q + 3], m_in[q].w);
+            st_off(p.master, vec * kF32Bytes + 16u * q, make_v4f(w[4 * q], w[4 * q + 1], w[4 * q + 2], w[4 * q + 3]));
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < E; ++e) w[e] = fmaf(-lr, g[e], newest[e]);
+    }
+    st_off(p.out, vec * (uint32_t)S::kRawBytes, S::narrow(w));
+    if (GOUT) {
+#pragma unroll
+        for (int q = 0; q < S::kF4; ++q)
+            st_off(p.g_out, vec * kF32Bytes + 16u * q, make_v4f(g[4 * q], g[4 * q + 1], g[4 * q + 2], g[4 * q + 3]));
+    }
+}
+
 // Finish one vector: iterate, update, store.  raw_g / raw_v hold the loaded inputs.
 template <typename S, int NV, bool COMP, bool NORMS, bool GOUT>
 __device__ __forceinline__ void finish_vector(const ChunkPtrs<NV> &p, uint32_t vec,
                                               const typename S::Raw &raw_g,
-                                              const typename S::Raw (&raw_v)[NV], const v4f (&m_in)[2],
+                                              const typename S::Raw (&raw_v)[NV], const v4f (&m_in)[S::kF4],
                                               float lambda, float lr, float (&acc)[3]) {
     constexpr int E = S::kElems;
     float g[E], prev[E], cur[E], first[E];
@@ -167,29 +234,7 @@ __device__ __forceinline__ void finish_vector(const ChunkPtrs<NV> &p, uint32_t v
             acc[2] = fmaf(gap, gap, acc[2]);
         }
     }
-    if constexpr (E == 4) {           // fp32 storage: update the newest version directly
-        v4f o;
-        o.x = fmaf(-lr, g[0], prev[0]); o.y = fmaf(-lr, g[1], prev[1]);
-        o.z = fmaf(-lr, g[2], prev[2]); o.w = fmaf(-lr, g[3], prev[3]);
-        st_off(p.out, vec * 16u, o);
-        if (GOUT) st_off(p.g_out, vec * 16u, make_v4f(g[0], g[1], g[2], g[3]));
-    } else {                          // bf16 storage: update the master, store its rounding
-        v4f m0 = m_in[0], m1 = m_in[1];
-        m0.x = fmaf(-lr, g[0], m0.x); m0.y = fmaf(-lr, g[1], m0.y);
-        m0.z = fmaf(-lr, g[2], m0.z); m0.w = fmaf(-lr, g[3], m0.w);
-        m1.x = fmaf(-lr, g[4], m1.x); m1.y = fmaf(-lr, g[5], m1.y);
-        m1.z = fmaf(-lr, g[6], m1.z); m1.w = fmaf(-lr, g[7], m1.w);
-        st_off(p.master, vec * 32u, m0);
-        st_off(p.master, vec * 32u + 16u, m1);
-        v4u o;
-        o.x = bf16_pack(m0.x, m0.y); o.y = bf16_pack(m0.z, m0.w);
-        o.z = bf16_pack(m1.x, m1.y); o.w = bf16_pack(m1.z, m1.w);
-        st_off(p.out, vec * 16u, o);
-        if (GOUT) {
-            st_off(p.g_out, vec * 32u, make_v4f(g[0], g[1], g[2], g[3]));
-            st_off(p.g_out, vec * 32u + 16u, make_v4f(g[4], g[5], g[6], g[7]));
-        }
-    }
+    update_and_store<S, NV, GOUT>(p, vec, g, prev, m_in, lr);
 }
 
 // A chunk with a compile-time number NV of versions to read.  Groups of kThreads*kUnroll vectors
@@ -201,44 +246,38 @@ template <typename S, int NV, bool COMP, bool NORMS, bool GOUT>
 __device__ __forceinline__ void run_chunk(const ChunkPtrs<NV> &p, uint32_t n_vecs, float lambda,
                                           float lr, float (&acc)[3]) {
     using Raw = typename S::Raw;
-    constexpr bool kMaster = S::kElems == 8;
+    constexpr uint32_t RB = S::kRawBytes;
     const uint32_t tid = threadIdx.x;
     const uint32_t group = kThreads * kUnroll;
     const uint32_t n_grouped = n_vecs / group * group;
 
     for (uint32_t base = 0; base < n_grouped; base += group) {
         Raw rg[kUnroll], rv[kUnroll][NV];
-        v4f m[kUnroll][2];
+        v4f m[kUnroll][S::kF4];
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) rg[u] = ld_off<Raw>(p.g, (base + u * kThreads + tid) * 16u);
+        for (int u = 0; u < kUnroll; ++u) rg[u] = ld_off<Raw>(p.g, (base + u * kThreads + tid) * RB);
 #pragma unroll
         for (int s = 0; s < NV; ++s)
 #pragma unroll
-            for (int u = 0; u < kUnroll; ++u) rv[u][s] = ld_off<Raw>(p.v[s], (base + u * kThreads + tid) * 16u);
-        if (kMaster) {
+            for (int u = 0; u < kUnroll; ++u) rv[u][s] = ld_off<Raw>(p.v[s], (base + u * kThreads + tid) * RB);
 #pragma unroll
-            for (int u = 0; u < kUnroll; ++u) {
-                const uint32_t off = (base + u * kThreads + tid) * 32u;
-                m[u][0] = ld_off<v4f>(p.master, off);
-                m[u][1] = ld_off<v4f>(p.master, off + 16u);
-            }
-        }
+        for (int u = 0; u < kUnroll; ++u) load_master<S>(p.master, base + u * kThreads + tid, m[u]);
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u)
             finish_vector<S, NV, COMP, NORMS, GOUT>(p, base + u * kThreads + tid, rg[u], rv[u], m[u], lambda,
                                                     lr, acc);
     }
     for (uint32_t vec = n_grouped + tid; vec < n_vecs; vec += kThreads) {
-        Raw rg = ld_off<Raw>(p.g, vec * 16u), rv[NV];
-        v4f m[2];
+        Raw rg = ld_off<Raw>(p.g, vec * RB), rv[NV];
+        v4f m[S::kF4];
 #pragma unroll
-        for (int s = 0; s < NV; ++s) rv[s] = ld_off<Raw>(p.v[s], vec * 16u);
-        if (kMaster) { m[0] = ld_off<v4f>(p.master, vec * 32u); m[1] = ld_off<v4f>(p.master, vec * 32u + 16u); }
+        for (int s = 0; s < NV; ++s) rv[s] = ld_off<Raw>(p.v[s], vec * RB);
+        load_master<S>(p.master, vec, m);
         finish_vector<S, NV, COMP, NORMS, GOUT>(p, vec, rg, rv, m, lambda, lr, acc);
     }
 }
 
-// Any number of versions (K' > 4): stream them one boundary at a time.  `arena` points at this
+// Any number of versions (K' > 8): stream them, four boundaries at a time.  `arena` points at this
 // chunk's first element in slot 0 of the stage; slots are slot_bytes apart.
 template <typename S, bool NORMS, bool GOUT>
 __device__ __forceinline__ void run_chunk_streamed(const ChunkPtrs<1> &p, const char *arena, uint64_t slot_bytes,
@@ -246,11 +285,14 @@ __device__ __forceinline__ void run_chunk_streamed(const ChunkPtrs<1> &p, const 
                                                    uint32_t n_vecs, float lambda, float lr, float (&acc)[3]) {
     using Raw = typename S::Raw;
     constexpr int E = S::kElems;
+    constexpr uint32_t RB = S::kRawBytes;
     const uint32_t oldest = (head + R - tau) % R;
     for (uint32_t vec = threadIdx.x; vec < n_vecs; vec += kThreads) {
         float g[E], prev[E], cur[E], first[E];
-        Raw rg = ld_off<Raw>(p.g, vec * 16u);
-        Raw r0 = ld_off<Raw>(arena + (uint64_t)oldest * slot_bytes, vec * 16u);
+        v4f m[S::kF4];
+        Raw rg = ld_off<Raw>(p.g, vec * RB);
+        Raw r0 = ld_off<Raw>(arena + (uint64_t)oldest * slot_bytes, vec * RB);
+        load_master<S>(p.master, vec, m);
         S::widen(rg, g);
         S::widen(r0, prev);
 #pragma unroll
@@ -265,7 +307,7 @@ __device__ __forceinline__ void run_chunk_streamed(const ChunkPtrs<1> &p, const 
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
                 const uint32_t s_i = (uint32_t)(((uint64_t)(i + b) * tau) / kp);
-                r[b] = ld_off<Raw>(arena + (uint64_t)((oldest + s_i) % R) * slot_bytes, vec * 16u);
+                r[b] = ld_off<Raw>(arena + (uint64_t)((oldest + s_i) % R) * slot_bytes, vec * RB);
             }
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
@@ -279,7 +321,7 @@ __device__ __forceinline__ void run_chunk_streamed(const ChunkPtrs<1> &p, const 
         }
         for (; i <= kp; ++i) {
             const uint32_t s_i = (uint32_t)(((uint64_t)i * tau) / kp);
-            Raw r = ld_off<Raw>(arena + (uint64_t)((oldest + s_i) % R) * slot_bytes, vec * 16u);
+            Raw r = ld_off<Raw>(arena + (uint64_t)((oldest + s_i) % R) * slot_bytes, vec * RB);
             S::widen(r, cur);
 #pragma unroll
             for (int e = 0; e < E; ++e) {
@@ -295,29 +337,7 @@ __device__ __forceinline__ void run_chunk_streamed(const ChunkPtrs<1> &p, const 
                 acc[2] = fmaf(gap, gap, acc[2]);
             }
         }
-        if constexpr (E == 4) {
-            v4f o;
-            o.x = fmaf(-lr, g[0], prev[0]); o.y = fmaf(-lr, g[1], prev[1]);
-            o.z = fmaf(-lr, g[2], prev[2]); o.w = fmaf(-lr, g[3], prev[3]);
-            st_off(p.out, vec * 16u, o);
-            if (GOUT) st_off(p.g_out, vec * 16u, make_v4f(g[0], g[1], g[2], g[3]));
-        } else {
-            v4f m0 = ld_off<v4f>(p.master, vec * 32u), m1 = ld_off<v4f>(p.master, vec * 32u + 16u);
-            m0.x = fmaf(-lr, g[0], m0.x); m0.y = fmaf(-lr, g[1], m0.y);
-            m0.z = fmaf(-lr, g[2], m0.z); m0.w = fmaf(-lr, g[3], m0.w);
-            m1.x = fmaf(-lr, g[4], m1.x); m1.y = fmaf(-lr, g[5], m1.y);
-            m1.z = fmaf(-lr, g[6], m1.z); m1.w = fmaf(-lr, g[7], m1.w);
-            st_off(p.master, vec * 32u, m0);
-            st_off(p.master, vec * 32u + 16u, m1);
-            v4u o;
-            o.x = bf16_pack(m0.x, m0.y); o.y = bf16_pack(m0.z, m0.w);
-            o.z = bf16_pack(m1.x, m1.y); o.w = bf16_pack(m1.z, m1.w);
-            st_off(p.out, vec * 16u, o);
-            if (GOUT) {
-                st_off(p.g_out, vec * 32u, make_v4f(g[0], g[1], g[2], g[3]));
-                st_off(p.g_out, vec * 32u + 16u, make_v4f(g[4], g[5], g[6], g[7]));
-            }
-        }
+        update_and_store<S, 1, GOUT>(p, vec, g, prev, m, lr);
     }
 }
 
@@ -339,7 +359,7 @@ struct ChunkInfo {
 
 template <typename S>
 __device__ __forceinline__ ChunkInfo chunk_info(const StepArgs &a, const StageDesc &d, uint32_t chunk) {
-    constexpr uint64_t kStoreBytes = 16 / S::kElems;
+    constexpr uint64_t kStoreBytes = S::kStoreBytes;
     ChunkInfo c;
     const uint64_t e0 = (uint64_t)(chunk - uniform(d.chunk_begin)) * a.chunk_elems;
     const uint64_t left = uniform(d.n_elems) - e0;
@@ -358,7 +378,7 @@ __device__ __forceinline__ ChunkInfo chunk_info(const StepArgs &a, const StageDe
 // Fixed-NV dispatch target: builds the chunk's pointers.
 template <typename S, int NV, bool COMP, bool NORMS, bool GOUT>
 __device__ __forceinline__ void do_chunk(const StepArgs &a, const ChunkInfo &c, float (&acc)[3]) {
-    constexpr uint64_t kStoreBytes = 16 / S::kElems;
+    constexpr uint64_t kStoreBytes = S::kStoreBytes;
     ChunkPtrs<NV> p;
     p.g = static_cast<const char *>(a.grads) + c.flat_elem0 * kStoreBytes;
     const uint32_t oldest = (c.head + c.R - c.tau) % c.R;
@@ -403,7 +423,7 @@ __device__ __forceinline__ void process_chunk(const StepArgs &a, const ChunkInfo
     } else if (LEVEL >= 1 && c.kp == 8) {
         do_chunk<S, 9, true, NORMS, GOUT>(a, c, acc);
     } else if (LEVEL >= 2) {
-        constexpr uint64_t kStoreBytes = 16 / S::kElems;
+        constexpr uint64_t kStoreBytes = S::kStoreBytes;
         ChunkPtrs<1> p;
         p.g = static_cast<const char *>(a.grads) + c.flat_elem0 * kStoreBytes;
         p.v[0] = nullptr;

@@ -86,7 +86,7 @@ def test_bf16_plan_sizes(lib):
     assert plan.precision == B.FERRET_BF16_MASTER_F32
     assert plan.ring_bytes == plan.ring_elems * 2 and plan.grad_bytes == plan.flat_elems * 2
     assert plan.master_bytes == plan.flat_elems * 4
-    assert plan.chunk_elems % 2048 == 0
+    assert plan.chunk_elems == 2048
 
 
 def test_minimal_ring_depth_is_paper_count(lib):
