@@ -186,3 +186,58 @@ int ferret_oracle_stage_bf16(int64_t n, int32_t n_versions, const uint16_t *cons
     if (norms) { norms[0] = sum_g0; norms[1] = sum_gk; norms[2] = sum_gap; }
     return 0;
 }
+
+/* ==== adaptive lambda (Alg. 1, block "update lambda") ===================================
+ *
+ * Before the iterations, when eta_lambda > 0, Alg. 1 takes one gradient-descent step on
+ *     || dv_r - lambda * v_a ||^2         (Eq. "lambda-objective-v1" with D - E and F
+ *                                          replaced by their moving averages)
+ * where, with the state BEFORE this call,
+ *     dv_r = (1 - alpha) * (g_0 - v_r)                          (the "D - E" equation)
+ *     d/dlambda ||dv_r - lambda v_a||^2 = -2 * < v_a, dv_r - lambda v_a >
+ *     lambda <- lambda - eta_lambda * that derivative
+ *             = lambda + 2 eta_lambda ( <v_a, dv_r> - lambda <v_a, v_a> )
+ * and then moves the two exponential moving averages
+ *     v_r <- alpha v_r + (1 - alpha) g_0
+ *     v_a <- alpha v_a + (1 - alpha) g_0 (.) g_0 (.) (V[1] - V[0])
+ * (V[1] - V[0] is the first version step after the snapshot the gradient was taken on).
+ * The l2 term of the objective does not appear in Alg. 1 and is not applied.
+ *
+ * Reading for tau = 0: no later version exists, the expression V[1] - V[0] is undefined
+ * and nothing is compensated, so the caller skips this block (state and lambda unchanged).
+ *
+ * State arrays are fp32 in storage; arithmetic is double, rounded once on output.
+ * v_r_new / v_a_new may alias v_r / v_a.  Returns the new lambda (unrounded double).
+ * `bf16` selects the storage type of g0 / V0 / V1 (uint16 bit patterns) versus fp32.
+ */
+static double widen_at(const void *p, int64_t e, int bf16)
+{
+    return bf16 ? (double)ferret_oracle_bf16_to_f32(((const uint16_t *)p)[e])
+                : (double)((const float *)p)[e];
+}
+
+double ferret_oracle_lambda_update(int64_t n, const void *g0, const void *V0, const void *V1,
+                                   int32_t bf16, double lambda, double alpha, double eta_lambda,
+                                   const float *v_r, const float *v_a,
+                                   float *v_r_new, float *v_a_new, double *sums /* nullable: <v_a,dv_r>, <v_a,v_a> */)
+{
+    double dot_a_dr = 0.0, dot_a_a = 0.0;
+    for (int64_t e = 0; e < n; ++e) {
+        double g = widen_at(g0, e, bf16);
+        double dv_r = (1.0 - alpha) * (g - (double)v_r[e]);
+        dot_a_dr += (double)v_a[e] * dv_r;
+        dot_a_a += (double)v_a[e] * (double)v_a[e];
+    }
+    double derivative = -2.0 * (dot_a_dr - lambda * dot_a_a);
+    double lambda_new = lambda - eta_lambda * derivative;
+    for (int64_t e = 0; e < n; ++e) {
+        double g = widen_at(g0, e, bf16);
+        double first_step = widen_at(V1, e, bf16) - widen_at(V0, e, bf16);
+        double r = alpha * (double)v_r[e] + (1.0 - alpha) * g;
+        double a = alpha * (double)v_a[e] + (1.0 - alpha) * (g * g * first_step);
+        v_r_new[e] = (float)r;
+        v_a_new[e] = (float)a;
+    }
+    if (sums) { sums[0] = dot_a_dr; sums[1] = dot_a_a; }
+    return lambda_new;
+}

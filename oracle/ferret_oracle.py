@@ -60,6 +60,11 @@ def _load():
             ctypes.c_int64, ctypes.c_int32, pp, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_int32, ctypes.c_double, ctypes.c_double, ctypes.c_void_p,
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32]
+        lib.ferret_oracle_lambda_update.restype = ctypes.c_double
+        lib.ferret_oracle_lambda_update.argtypes = [
+            ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32,
+            ctypes.c_double, ctypes.c_double, ctypes.c_double, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
         _lib = lib
     return _lib
 
@@ -150,6 +155,46 @@ def compensate_stage_bf16(versions, g0, master, K: int, lam: float, eta: float,
     if rc != 0:
         raise ValueError("ferret_oracle_stage_bf16: bad arguments")
     return out, m_out, g_out, norms
+
+
+# ---- adaptive lambda (Alg. 1 with eta_lambda > 0) ------------------------------------------
+def lambda_update(g0, V0, V1, lam: float, alpha: float, eta_lambda: float, v_r, v_a, bf16: bool = False):
+    """The "update lambda" block of Alg. 1 on one stage.  Returns (lambda_new, v_r_new, v_a_new, sums)
+    with sums = (<v_a, dv_r>, <v_a, v_a>) taken on the state before the call."""
+    dt = np.uint16 if bf16 else np.float32
+    g, a0, a1 = _as_np(g0, dt), _as_np(V0, dt), _as_np(V1, dt)
+    r, a = _as_np(v_r, np.float32), _as_np(v_a, np.float32)
+    n = g.size
+    if not (a0.size == a1.size == r.size == a.size == n):
+        raise ValueError("size mismatch")
+    r_new, a_new = np.empty(n, np.float32), np.empty(n, np.float32)
+    sums = np.zeros(2, np.float64)
+    lam_new = _load().ferret_oracle_lambda_update(
+        n, g.ctypes.data, a0.ctypes.data, a1.ctypes.data, int(bf16), float(lam), float(alpha),
+        float(eta_lambda), r.ctypes.data, a.ctypes.data, r_new.ctypes.data, a_new.ctypes.data,
+        sums.ctypes.data)
+    return float(lam_new), r_new, a_new, sums
+
+
+def compensate_stage_adaptive(versions, g0, master, K: int, lam: float, alpha: float, eta_lambda: float,
+                              eta: float, v_r, v_a, bf16: bool = False, n_threads: int = 1):
+    """All of Alg. 1 for one stage: lambda block (skipped when eta_lambda = 0 or tau = 0), then the
+    iterations with the NEW lambda, then the update.  Returns a dict."""
+    tau = len(versions) - 1
+    if eta_lambda > 0 and tau >= 1:
+        lam_new, r_new, a_new, sums = lambda_update(g0, versions[0], versions[1], lam, alpha, eta_lambda,
+                                                    v_r, v_a, bf16)
+    else:
+        lam_new, sums = float(lam), np.zeros(2)
+        r_new, a_new = _as_np(v_r, np.float32).copy(), _as_np(v_a, np.float32).copy()
+    out = dict(lam=lam_new, v_r=r_new, v_a=a_new, sums=sums)
+    if bf16:
+        new, m_new, g_out, norms = compensate_stage_bf16(versions, g0, master, K, lam_new, eta, n_threads)
+        out.update(new=new, master=m_new, g=g_out, norms=norms)
+    else:
+        new, g_out, norms = compensate_stage_f32(versions, g0, K, lam_new, eta, n_threads)
+        out.update(new=new, g=g_out, norms=norms)
+    return out
 
 
 # ---- version store across steps ---------------------------------------------------------
