@@ -201,6 +201,41 @@ ferret_status ferret_compensate_step(const ferret_plan *plan, void *ring, const 
                                      float *master, float lambda, float lr, float *norms_out,
                                      void *grad_out, void *workspace, void *hip_stream);
 
+/* ---- the step with self-tuned lambda --------------------------------------------------------- */
+/* All of Alg. 1 including its "update lambda" block (Sec. "Iterative Gradient Compensation", Eq.
+ * "lambda-objective-v1" and the moving averages after it).  Per stage j with effective staleness
+ * >= 1, in this order and with the state as it is BEFORE the call:
+ *     dv_r     = (1 - alpha) (g_0 - v_r)
+ *     lambda_j = lambda_j + 2 eta_lambda ( <v_a, dv_r> - lambda_j <v_a, v_a> )
+ *                (one gradient-descent step on || dv_r - lambda v_a ||^2; sums over the stage)
+ *     v_r      = alpha v_r + (1 - alpha) g_0
+ *     v_a      = alpha v_a + (1 - alpha) g_0 (.) g_0 (.) (V[1] - V[0])
+ * and then the iterations and the update of ferret_compensate_step with the NEW lambda_j.
+ * Stages whose effective staleness is 0 have nothing to compensate: their lambda_j, v_r, v_a stay
+ * untouched.  The l2 term of the paper's objective is not part of Alg. 1 and is not applied.
+ *   lambda       device float[n_stages], read and updated in place (one coefficient per stage:
+ *                every stage runs its own instance of the algorithm)
+ *   v_r, v_a     device fp32 flat buffers, updated in place; zero them before the first step
+ *   alpha        moving-average coefficient, 0 <= alpha < 1
+ *   eta_lambda   learning rate of lambda, >= 0 (0 leaves lambda and the averages untouched)
+ * Other arguments as in ferret_compensate_step.  `workspace` is always required here (the two
+ * inner products go through it before the norms do).  FERRET_EINVAL if the plan has n_iters = 0.
+ * Implementation: one pass over g_0, v_r, v_a, V[0], V[1] that forms the two sums and the new
+ * averages (28 bytes per fp32 parameter), a tiny kernel that steps lambda, then the same fused
+ * kernel as ferret_compensate_step reading lambda_j from device memory. */
+typedef struct {
+    float *lambda;
+    float *v_r;
+    float *v_a;
+    float alpha;
+    float eta_lambda;
+} ferret_adaptive;
+
+ferret_status ferret_compensate_step_adaptive(const ferret_plan *plan, void *ring, const void *grads,
+                                              float *master, const ferret_adaptive *adaptive, float lr,
+                                              float *norms_out, void *grad_out, void *workspace,
+                                              void *hip_stream);
+
 /* ---- misc ------------------------------------------------------------------------------------ */
 const char *ferret_last_error(void);   /* message of the calling thread's last failed call */
 const char *ferret_version(void);

@@ -41,6 +41,11 @@ class ferret_tuning(ctypes.Structure):
                 ("blocks_per_cu", c_int32), ("resident_cap", c_int32)]
 
 
+class ferret_adaptive(ctypes.Structure):
+    _fields_ = [("lambda_", c_void_p), ("v_r", c_void_p), ("v_a", c_void_p), ("alpha", c_float),
+                ("eta_lambda", c_float)]
+
+
 class FerretError(RuntimeError):
     def __init__(self, status: int, message: str):
         super().__init__(f"{STATUS_NAMES.get(status, status)}: {message}")
@@ -87,6 +92,7 @@ SIGNATURES = {
     "ferret_plan_step_bytes": (c_int64, [_P]),
     "ferret_push_version": (c_int32, [_P, _P, _P, c_int32, _P, _P]),
     "ferret_compensate_step": (c_int32, [_P, _P, _P, _P, c_float, c_float, _P, _P, _P, _P]),
+    "ferret_compensate_step_adaptive": (c_int32, [_P, _P, _P, _P, POINTER(ferret_adaptive), c_float, _P, _P, _P, _P]),
     "ferret_last_error": (c_char_p, []),
     "ferret_version": (c_char_p, []),
     "ferret_copy_bytes": (c_int32, [_P, _P, c_size_t, _P]),
@@ -172,6 +178,15 @@ def ferret_compensate_step(plan: "Plan", ring, grads, master, lam: float, lr: fl
     _check(load().ferret_compensate_step(plan.handle, _ptr(ring), _ptr(grads), _ptr(master), lam, lr,
                                          _ptr(norms_out), _ptr(grad_out), _ptr(workspace),
                                          _stream(stream)))
+
+
+def ferret_compensate_step_adaptive(plan: "Plan", ring, grads, master, lambda_dev, v_r, v_a, alpha: float,
+                                    eta_lambda: float, lr: float, norms_out=None, grad_out=None,
+                                    workspace=None, stream=None) -> None:
+    ad = ferret_adaptive(_ptr(lambda_dev), _ptr(v_r), _ptr(v_a), alpha, eta_lambda)
+    _check(load().ferret_compensate_step_adaptive(plan.handle, _ptr(ring), _ptr(grads), _ptr(master), byref(ad), lr,
+                                                  _ptr(norms_out), _ptr(grad_out), _ptr(workspace),
+                                                  _stream(stream)))
 
 
 def ferret_copy_bytes(dst, src, n_bytes: int, stream=None) -> None:
@@ -342,6 +357,21 @@ class DeviceState:
                                self.norms if norms else None,
                                self.grad_out if grad_out else None,
                                self.workspace if norms else None, stream)
+
+    def enable_adaptive(self, lambda0: float) -> None:
+        """Allocate the self-tuning state: lambda_j = lambda0, v_r = v_a = 0 (Alg. 1, initialisation)."""
+        z = dict(device=self.device, dtype=torch.float32)
+        self.lambda_dev = torch.full((self.plan.n_stages,), float(lambda0), **z)
+        self.v_r = torch.zeros(self.plan.flat_elems, **z)
+        self.v_a = torch.zeros(self.plan.flat_elems, **z)
+        if self.workspace is None:
+            self.workspace = torch.zeros(max(self.plan.workspace_bytes // 4, 4), **z)
+
+    def step_adaptive(self, alpha: float, eta_lambda: float, lr: float, norms: bool = True, grad_out: bool = True,
+                      stream=None) -> None:
+        ferret_compensate_step_adaptive(self.plan, self.ring, self.grads, self.master, self.lambda_dev, self.v_r,
+                                        self.v_a, alpha, eta_lambda, lr, self.norms if norms else None,
+                                        self.grad_out if grad_out else None, self.workspace, stream)
 
     def commit(self, stage: int = -1) -> None:
         ferret_push_version(self.plan, self.ring, None, stage, None)

@@ -355,25 +355,28 @@ ferret_status ferret_push_version(ferret_plan *plan, void *ring, float *master, 
 }
 
 // ---- step --------------------------------------------------------------------------------------
-ferret_status ferret_compensate_step(const ferret_plan *plan, void *ring, const void *grads, float *master,
-                                     float lambda, float lr, float *norms_out, void *grad_out,
-                                     void *workspace, void *hip_stream) {
-    if (!plan || !ring || !grads) { set_error("compensate_step: null plan, ring or grads"); return FERRET_EINVAL; }
+static ferret_status check_step_args(const char *who, const ferret_plan *plan, void *ring, const void *grads,
+                                     float *master, float *norms_out, void *grad_out, void *workspace) {
+    if (!plan || !ring || !grads) { set_error("%s: null plan, ring or grads", who); return FERRET_EINVAL; }
     const bool mixed = plan->prec == FERRET_BF16_MASTER_F32;
-    if (mixed && !master) { set_error("compensate_step: bf16 plan needs the fp32 master"); return FERRET_EINVAL; }
-    if (!mixed && master) { set_error("compensate_step: master given but the plan is fp32"); return FERRET_EINVAL; }
-    if (norms_out && !workspace) { set_error("compensate_step: norms_out needs workspace"); return FERRET_EINVAL; }
+    if (mixed && !master) { set_error("%s: bf16 plan needs the fp32 master", who); return FERRET_EINVAL; }
+    if (!mixed && master) { set_error("%s: master given but the plan is fp32", who); return FERRET_EINVAL; }
+    if (norms_out && !workspace) { set_error("%s: norms_out needs workspace", who); return FERRET_EINVAL; }
     if (!aligned16(ring) || !aligned16(grads) || !aligned16(master) || !aligned16(grad_out) ||
         !aligned16(workspace) || (reinterpret_cast<uintptr_t>(norms_out) & 3u)) {
-        set_error("compensate_step: device pointers must be 16-byte aligned"); return FERRET_EINVAL;
+        set_error("%s: device pointers must be 16-byte aligned", who); return FERRET_EINVAL;
     }
     for (size_t j = 0; j < plan->stages.size(); ++j)
         if (plan->stages[j].valid < 1) {
-            set_error("compensate_step: stage %zu holds no weight version yet (push one first)", j);
+            set_error("%s: stage %zu holds no weight version yet (push one first)", who, j);
             return FERRET_ESTATE;
         }
+    return FERRET_OK;
+}
 
-    StepArgs a;
+static void fill_step_args(const ferret_plan *plan, StepArgs &a, void *ring, const void *grads, float *master,
+                           float lambda, float lr, float *norms_out, void *grad_out, void *workspace) {
+    memset(&a, 0, sizeof a);
     a.ring = ring;
     a.grads = grads;
     a.master = master;
@@ -384,13 +387,60 @@ ferret_status ferret_compensate_step(const ferret_plan *plan, void *ring, const 
     a.n_stages = (uint32_t)plan->stages.size();
     a.n_chunks = (uint32_t)plan->n_chunks;
     a.chunk_elems = (uint32_t)plan->chunk_elems;
-    a.pad_ = 0;
     fill_step_descs(*plan, a.stage);
     for (uint32_t j = 0; j < FERRET_MAX_STAGES; ++j)
         a.chunk_begin[j] = j < a.n_stages ? a.stage[j].chunk_begin : UINT32_MAX;
+}
+
+ferret_status ferret_compensate_step(const ferret_plan *plan, void *ring, const void *grads, float *master,
+                                     float lambda, float lr, float *norms_out, void *grad_out,
+                                     void *workspace, void *hip_stream) {
+    ferret_status rc = check_step_args("compensate_step", plan, ring, grads, master, norms_out, grad_out, workspace);
+    if (rc != FERRET_OK) return rc;
+    StepArgs a;
+    fill_step_args(plan, a, ring, grads, master, lambda, lr, norms_out, grad_out, workspace);
     int err = launch_step(*plan, a, norms_out, hip_stream);
     if (err) { set_error("compensate_step: launch failed: %s", device_error_string(err)); return FERRET_EDEVICE; }
     // bookkeeping only: remembers that slot head+1 now holds an uncommitted version
+    for (const Stage &s : plan->stages) s.step_pending = true;
+    return FERRET_OK;
+}
+
+ferret_status ferret_compensate_step_adaptive(const ferret_plan *plan, void *ring, const void *grads,
+                                              float *master, const ferret_adaptive *ad, float lr,
+                                              float *norms_out, void *grad_out, void *workspace,
+                                              void *hip_stream) {
+    const char *who = "compensate_step_adaptive";
+    ferret_status rc = check_step_args(who, plan, ring, grads, master, norms_out, grad_out, workspace);
+    if (rc != FERRET_OK) return rc;
+    if (!ad || !ad->lambda || !ad->v_r || !ad->v_a || !workspace) {
+        set_error("%s: null adaptive state (lambda, v_r, v_a) or workspace", who); return FERRET_EINVAL;
+    }
+    if (!aligned16(ad->v_r) || !aligned16(ad->v_a) || (reinterpret_cast<uintptr_t>(ad->lambda) & 3u)) {
+        set_error("%s: v_r and v_a must be 16-byte aligned, lambda 4-byte aligned", who); return FERRET_EINVAL;
+    }
+    if (!(ad->alpha >= 0.f && ad->alpha < 1.f) || !(ad->eta_lambda >= 0.f)) {
+        set_error("%s: need 0 <= alpha < 1 and eta_lambda >= 0 (got %g, %g)", who, (double)ad->alpha,
+                  (double)ad->eta_lambda);
+        return FERRET_EINVAL;
+    }
+    if (plan->n_iters == 0) { set_error("%s: the plan has n_iters = 0, there is nothing for lambda to scale", who); return FERRET_EINVAL; }
+    StepArgs a;
+    fill_step_args(plan, a, ring, grads, master, 0.f, lr, norms_out, grad_out, workspace);
+    a.lambda_dev = ad->lambda;
+    a.v_r = ad->v_r;
+    a.v_a = ad->v_a;
+    a.alpha = ad->alpha;
+    a.eta_lambda = ad->eta_lambda;
+    int err = 0;
+    if (ad->eta_lambda > 0.f) {
+        float *step_partials = a.partials;
+        a.partials = static_cast<float *>(workspace);
+        err = launch_lambda_update(*plan, a, hip_stream);
+        a.partials = step_partials;
+    }
+    if (!err) err = launch_step(*plan, a, norms_out, hip_stream);
+    if (err) { set_error("%s: launch failed: %s", who, device_error_string(err)); return FERRET_EDEVICE; }
     for (const Stage &s : plan->stages) s.step_pending = true;
     return FERRET_OK;
 }

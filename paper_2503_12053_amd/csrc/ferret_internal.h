@@ -46,12 +46,18 @@ struct StepArgs {
     uint32_t n_chunks;
     uint32_t chunk_elems;
     uint32_t pad_;
+    // self-tuned lambda (null / zero for the fixed-lambda step)
+    float *lambda_dev;   // float[n_stages]; when set, stage j uses lambda_dev[j] instead of `lambda`
+    float *v_r;
+    float *v_a;
+    float alpha;
+    float eta_lambda;
     // chunk_begin of every stage again, densely packed (unused entries = UINT32_MAX), so that a
     // workgroup can find its chunk's stage with a few wide scalar loads
     uint32_t chunk_begin[FERRET_MAX_STAGES];
     StageDesc stage[FERRET_MAX_STAGES];
 };
-static_assert(sizeof(StepArgs) <= 3400, "StepArgs must fit the kernel-argument segment");
+static_assert(sizeof(StepArgs) <= 3600, "StepArgs must fit the kernel-argument segment");
 
 struct PushArgs {
     void *ring;
@@ -113,6 +119,7 @@ inline int32_t effective_iters(int32_t n_iters, int32_t tau) {
 
 // launchers implemented in ferret_kernels.hip; return hipError_t as int (0 = success)
 int launch_step(const ferret_plan &plan, const StepArgs &args, float *norms_out, void *stream);
+int launch_lambda_update(const ferret_plan &plan, const StepArgs &args, void *stream);
 int launch_push(const ferret_plan &plan, const PushArgs &args, void *stream);
 int launch_copy(void *dst, const void *src, size_t n_bytes, void *stream);
 const char *device_error_string(int err);

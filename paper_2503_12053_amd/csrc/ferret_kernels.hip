@@ -355,10 +355,12 @@ struct ChunkInfo {
     uint64_t flat_elem0;     // this chunk's first element in slot-shaped buffers
     uint32_t n_vecs;         // 16-byte storage vectors in the chunk
     uint32_t R, head, tau, kp;
+    uint32_t stage;
 };
 
 template <typename S>
-__device__ __forceinline__ ChunkInfo chunk_info(const StepArgs &a, const StageDesc &d, uint32_t chunk) {
+__device__ __forceinline__ ChunkInfo chunk_info(const StepArgs &a, const StageDesc &d, uint32_t chunk,
+                                                uint32_t stage) {
     constexpr uint64_t kStoreBytes = S::kStoreBytes;
     ChunkInfo c;
     const uint64_t e0 = (uint64_t)(chunk - uniform(d.chunk_begin)) * a.chunk_elems;
@@ -372,12 +374,13 @@ __device__ __forceinline__ ChunkInfo chunk_info(const StepArgs &a, const StageDe
     c.slot_bytes = uniform(d.slot_stride) * kStoreBytes;
     c.arena = static_cast<const char *>(a.ring) + (uniform(d.ring_base) + e0) * kStoreBytes;
     c.flat_elem0 = uniform(d.flat_off) + e0;
+    c.stage = stage;
     return c;
 }
 
 // Fixed-NV dispatch target: builds the chunk's pointers.
 template <typename S, int NV, bool COMP, bool NORMS, bool GOUT>
-__device__ __forceinline__ void do_chunk(const StepArgs &a, const ChunkInfo &c, float (&acc)[3]) {
+__device__ __forceinline__ void do_chunk(const StepArgs &a, const ChunkInfo &c, float lambda, float (&acc)[3]) {
     constexpr uint64_t kStoreBytes = S::kStoreBytes;
     ChunkPtrs<NV> p;
     p.g = static_cast<const char *>(a.grads) + c.flat_elem0 * kStoreBytes;
@@ -392,7 +395,7 @@ __device__ __forceinline__ void do_chunk(const StepArgs &a, const ChunkInfo &c, 
     p.out = const_cast<char *>(c.arena) + (uint64_t)((c.head + 1) % c.R) * c.slot_bytes;
     p.master = a.master ? reinterpret_cast<char *>(a.master) + c.flat_elem0 * 4 : nullptr;
     p.g_out = GOUT ? reinterpret_cast<char *>(a.grad_out) + c.flat_elem0 * 4 : nullptr;
-    run_chunk<S, NV, COMP, NORMS, GOUT>(p, c.n_vecs, a.lambda, a.lr, acc);
+    run_chunk<S, NV, COMP, NORMS, GOUT>(p, c.n_vecs, lambda, a.lr, acc);
 }
 
 // One chunk, whatever its K': picks the unrolled variant (K' <= 4 or <= 8) or the streamed one, then
@@ -401,27 +404,29 @@ template <typename S, int LEVEL, bool NORMS, bool GOUT>
 __device__ __forceinline__ void process_chunk(const StepArgs &a, const ChunkInfo &c, uint32_t chunk,
                                               float (&red)[3][kWaves]) {
     float acc[3] = {0.f, 0.f, 0.f};
+    // the coefficient: one scalar for the call, or this stage's self-tuned one from device memory
+    const float lambda = a.lambda_dev ? a.lambda_dev[c.stage] : a.lambda;
     // versions to read: the K'+1 boundaries; with K' = 0 only V[tau], plus V[0] when the weight
     // gap is wanted for the norms
     if (c.kp == 0) {
-        if (NORMS && c.tau > 0) do_chunk<S, 2, false, NORMS, GOUT>(a, c, acc);
-        else do_chunk<S, 1, false, NORMS, GOUT>(a, c, acc);
+        if (NORMS && c.tau > 0) do_chunk<S, 2, false, NORMS, GOUT>(a, c, lambda, acc);
+        else do_chunk<S, 1, false, NORMS, GOUT>(a, c, lambda, acc);
     } else if (c.kp == 1) {
-        do_chunk<S, 2, true, NORMS, GOUT>(a, c, acc);
+        do_chunk<S, 2, true, NORMS, GOUT>(a, c, lambda, acc);
     } else if (c.kp == 2) {
-        do_chunk<S, 3, true, NORMS, GOUT>(a, c, acc);
+        do_chunk<S, 3, true, NORMS, GOUT>(a, c, lambda, acc);
     } else if (c.kp == 3) {
-        do_chunk<S, 4, true, NORMS, GOUT>(a, c, acc);
+        do_chunk<S, 4, true, NORMS, GOUT>(a, c, lambda, acc);
     } else if (c.kp == 4) {
-        do_chunk<S, 5, true, NORMS, GOUT>(a, c, acc);
+        do_chunk<S, 5, true, NORMS, GOUT>(a, c, lambda, acc);
     } else if (LEVEL >= 1 && c.kp == 5) {
-        do_chunk<S, 6, true, NORMS, GOUT>(a, c, acc);
+        do_chunk<S, 6, true, NORMS, GOUT>(a, c, lambda, acc);
     } else if (LEVEL >= 1 && c.kp == 6) {
-        do_chunk<S, 7, true, NORMS, GOUT>(a, c, acc);
+        do_chunk<S, 7, true, NORMS, GOUT>(a, c, lambda, acc);
     } else if (LEVEL >= 1 && c.kp == 7) {
-        do_chunk<S, 8, true, NORMS, GOUT>(a, c, acc);
+        do_chunk<S, 8, true, NORMS, GOUT>(a, c, lambda, acc);
     } else if (LEVEL >= 1 && c.kp == 8) {
-        do_chunk<S, 9, true, NORMS, GOUT>(a, c, acc);
+        do_chunk<S, 9, true, NORMS, GOUT>(a, c, lambda, acc);
     } else if (LEVEL >= 2) {
         constexpr uint64_t kStoreBytes = S::kStoreBytes;
         ChunkPtrs<1> p;
@@ -431,7 +436,7 @@ __device__ __forceinline__ void process_chunk(const StepArgs &a, const ChunkInfo
         p.master = a.master ? reinterpret_cast<char *>(a.master) + c.flat_elem0 * 4 : nullptr;
         p.g_out = GOUT ? reinterpret_cast<char *>(a.grad_out) + c.flat_elem0 * 4 : nullptr;
         run_chunk_streamed<S, NORMS, GOUT>(p, c.arena, c.slot_bytes, c.R, c.head, c.tau, c.kp, c.n_vecs,
-                                           a.lambda, a.lr, acc);
+                                           lambda, a.lr, acc);
     }
     if (NORMS) {
         const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
@@ -474,7 +479,7 @@ __global__ void __launch_bounds__(kThreads) step_kernel(const StepArgs a) {
         for (uint32_t chunk = blockIdx.x; chunk < a.n_chunks; chunk += gridDim.x) {
             while (stage + 1 < a.n_stages && chunk >= tab[stage + 1].chunk_begin) ++stage;
             stage = uniform(stage);
-            const ChunkInfo c = chunk_info<S>(a, tab[stage], chunk);
+            const ChunkInfo c = chunk_info<S>(a, tab[stage], chunk, stage);
             process_chunk<S, LEVEL, NORMS, GOUT>(a, c, chunk, red);
             if (NORMS) __syncthreads();     // red[] is reused by the next chunk
         }
@@ -489,8 +494,105 @@ __global__ void __launch_bounds__(kThreads) step_kernel(const StepArgs a) {
 #pragma unroll
             for (uint32_t j = 16; j < FERRET_MAX_STAGES; ++j) stage += chunk >= a.chunk_begin[j] ? 1u : 0u;
         }
-        const ChunkInfo c = chunk_info<S>(a, a.stage[stage], chunk);
+        const ChunkInfo c = chunk_info<S>(a, a.stage[stage], chunk, stage);
         process_chunk<S, LEVEL, NORMS, GOUT>(a, c, chunk, red);
+    }
+}
+
+// ---- self-tuned lambda: state pass + lambda step ---------------------------------------------------
+// Alg. 1, block "update lambda", for every stage with staleness >= 1, one workgroup per chunk:
+// forms the chunk's share of <v_a, g_0 - v_r> and <v_a, v_a> on the OLD averages and writes the new
+// ones, v_r <- alpha v_r + (1-alpha) g_0 and v_a <- alpha v_a + (1-alpha) g_0 g_0 (V[1]-V[0]).
+// Reads g_0, V[0], V[1] (storage type) and v_r, v_a (fp32) once each: 28 bytes per fp32 parameter.
+template <typename S>
+__global__ void __launch_bounds__(kThreads) lambda_state_kernel(const StepArgs a) {
+    using Raw = typename S::Raw;
+    constexpr int E = S::kElems;
+    constexpr uint32_t RB = S::kRawBytes, FB = E * 4;
+    __shared__ float red[2][kWaves];
+    const uint32_t chunk = blockIdx.x;
+    uint32_t stage = 0;
+#pragma unroll
+    for (uint32_t j = 1; j < 16; ++j) stage += chunk >= a.chunk_begin[j] ? 1u : 0u;
+    if (a.n_stages > 16) {
+#pragma unroll
+        for (uint32_t j = 16; j < FERRET_MAX_STAGES; ++j) stage += chunk >= a.chunk_begin[j] ? 1u : 0u;
+    }
+    const ChunkInfo c = chunk_info<S>(a, a.stage[stage], chunk, stage);
+    float acc0 = 0.f, acc1 = 0.f;
+    if (c.tau >= 1) {       // uniform over the workgroup
+        const uint32_t oldest = (c.head + c.R - c.tau) % c.R;
+        const char *g_ptr = static_cast<const char *>(a.grads) + c.flat_elem0 * S::kStoreBytes;
+        const char *v0 = c.arena + (uint64_t)oldest * c.slot_bytes;
+        const char *v1 = c.arena + (uint64_t)((oldest + 1) % c.R) * c.slot_bytes;
+        char *vr_ptr = reinterpret_cast<char *>(a.v_r) + c.flat_elem0 * 4;
+        char *va_ptr = reinterpret_cast<char *>(a.v_a) + c.flat_elem0 * 4;
+        const float alpha = a.alpha, beta = 1.0f - a.alpha;
+        for (uint32_t vec = threadIdx.x; vec < c.n_vecs; vec += kThreads) {
+            const Raw rg = ld_off<Raw>(g_ptr, vec * RB), r0 = ld_off<Raw>(v0, vec * RB),
+                      r1 = ld_off<Raw>(v1, vec * RB);
+            v4f vr[S::kF4], va[S::kF4];
+#pragma unroll
+            for (int q = 0; q < S::kF4; ++q) {
+                vr[q] = ld_off<v4f>(vr_ptr, vec * FB + 16u * q);
+                va[q] = ld_off<v4f>(va_ptr, vec * FB + 16u * q);
+            }
+            float g[E], w0[E], w1[E];
+            S::widen(rg, g);
+            S::widen(r0, w0);
+            S::widen(r1, w1);
+#pragma unroll
+            for (int q = 0; q < S::kF4; ++q) {
+                float r[4] = {vr[q].x, vr[q].y, vr[q].z, vr[q].w}, s4[4] = {va[q].x, va[q].y, va[q].z, va[q].w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float gi = g[4 * q + i];
+                    acc0 = fmaf(s4[i], gi - r[i], acc0);
+                    acc1 = fmaf(s4[i], s4[i], acc1);
+                    r[i] = fmaf(alpha, r[i], beta * gi);
+                    s4[i] = fmaf(alpha, s4[i], beta * (gi * gi * (w1[4 * q + i] - w0[4 * q + i])));
+                }
+                st_off(vr_ptr, vec * FB + 16u * q, make_v4f(r[0], r[1], r[2], r[3]));
+                st_off(va_ptr, vec * FB + 16u * q, make_v4f(s4[0], s4[1], s4[2], s4[3]));
+            }
+        }
+    }
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    const float s0 = wave_sum(acc0), s1 = wave_sum(acc1);
+    if (lane == 0) { red[0][wave] = s0; red[1][wave] = s1; }
+    __syncthreads();
+    if (threadIdx.x < 2) {
+        float s = 0.f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) s += red[threadIdx.x][w];
+        a.partials[(size_t)threadIdx.x * a.n_chunks + chunk] = s;
+    }
+}
+
+// One workgroup per stage: sums the stage's two series in fp64 in a fixed order and takes the
+// gradient-descent step  lambda <- lambda + 2 eta_lambda ((1-alpha) <v_a, g_0 - v_r> - lambda <v_a, v_a>).
+constexpr int kLambdaThreads = 1024;
+__global__ void __launch_bounds__(kLambdaThreads) lambda_step_kernel(const StepArgs a) {
+    __shared__ double red[2][kLambdaThreads / 64];
+    const uint32_t j = blockIdx.x;
+    if (a.stage[j].tau == 0) return;
+    const uint32_t c0 = a.stage[j].chunk_begin;
+    const uint32_t c1 = j + 1 < a.n_stages ? a.stage[j + 1].chunk_begin : a.n_chunks;
+    double s0 = 0.0, s1 = 0.0;
+    for (uint32_t c = c0 + threadIdx.x; c < c1; c += kLambdaThreads) {
+        s0 += (double)a.partials[c];
+        s1 += (double)a.partials[(size_t)a.n_chunks + c];
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) { s0 += __shfl_xor(s0, off, 64); s1 += __shfl_xor(s1, off, 64); }
+    if ((threadIdx.x & 63u) == 0) { red[0][threadIdx.x >> 6] = s0; red[1][threadIdx.x >> 6] = s1; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double dot_a_dr = 0.0, dot_a_a = 0.0;
+        for (int w = 0; w < kLambdaThreads / 64; ++w) { dot_a_dr += red[0][w]; dot_a_a += red[1][w]; }
+        dot_a_dr *= (double)(1.0f - a.alpha);
+        const double lambda = (double)a.lambda_dev[j];
+        a.lambda_dev[j] = (float)(lambda + 2.0 * (double)a.eta_lambda * (dot_a_dr - lambda * dot_a_a));
     }
 }
 
@@ -718,6 +820,19 @@ int launch_step(const ferret_plan &plan, const StepArgs &a, float *norms_out, vo
         e = hipGetLastError();
     }
     return (int)e;
+}
+
+int launch_lambda_update(const ferret_plan &plan, const StepArgs &a, void *stream) {
+    if (a.n_chunks == 0) return 0;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (plan.prec == FERRET_F32)
+        hipLaunchKernelGGL(lambda_state_kernel<F32Store>, dim3(a.n_chunks), dim3(kThreads), 0, st, a);
+    else
+        hipLaunchKernelGGL(lambda_state_kernel<Bf16Store>, dim3(a.n_chunks), dim3(kThreads), 0, st, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return (int)e;
+    hipLaunchKernelGGL(lambda_step_kernel, dim3(a.n_stages), dim3(kLambdaThreads), 0, st, a);
+    return (int)hipGetLastError();
 }
 
 int launch_push(const ferret_plan &plan, const PushArgs &a, void *stream) {

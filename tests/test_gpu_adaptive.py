@@ -1,0 +1,135 @@
+"""GPU parity of the self-tuned-lambda step (all of Alg. 1) against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ferret_oracle as O
+from paper_2503_12053_amd import binding as B
+from paper_2503_12053_amd import workloads as W
+
+import parity_util as PU
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _gpu():
+    if not torch.cuda.is_available():
+        pytest.fail("these tests need a GPU")
+    B.load()
+
+
+def _state(w, st, seed, lam0):
+    """Random non-trivial averages so that the first step already moves lambda."""
+    st.enable_adaptive(lam0)
+    host = []
+    for j, n in enumerate(w.stage_numel()):
+        g = torch.Generator().manual_seed(seed * 100 + j)
+        vr = torch.randn(n, generator=g)
+        va = torch.randn(n, generator=g) * 0.05
+        st.set_flat(st.v_r, j, vr)
+        st.set_flat(st.v_a, j, va)
+        host.append((vr.numpy().copy(), va.numpy().copy()))
+    return host
+
+
+def _check(w, plan, st, host, state, lams, alpha, eta_l, K, tag):
+    norms = st.norms.cpu().numpy().astype(np.float64)
+    lam_gpu = st.lambda_dev.cpu().numpy()
+    new_state, new_lams = [], []
+    bf16 = w.precision == "bf16"
+    for j in range(w.n_stages):
+        tau = plan.stage_effective_staleness(j)
+        d = host[j]
+        window = d.versions[len(d.versions) - 1 - tau:]
+        ref = O.compensate_stage_adaptive(window, d.grads, d.master, K, lams[j], np.float32(alpha), np.float32(eta_l),
+                                          np.float32(w.lr), state[j][0], state[j][1], bf16=bf16)
+        t = f"{tag} stage {j}"
+        assert lam_gpu[j] == pytest.approx(ref["lam"], rel=1e-5), t + " lambda"
+        if tau == 0:
+            assert lam_gpu[j] == np.float32(lams[j])
+        got_r, got_a = st.get_flat(st.v_r, j).numpy(), st.get_flat(st.v_a, j).numpy()
+        PU.assert_close_f32(got_r, ref["v_r"], t + " v_r")
+        PU.assert_close_f32(got_a, ref["v_a"], t + " v_a")
+        PU.assert_close_f32(st.get_flat(st.grad_out, j).numpy(), ref["g"], t + " g_K'")
+        slot = plan.stage_write_slot(j)
+        if bf16:
+            got_m = st.get_flat(st.master, j).numpy()
+            PU.assert_close_f32(got_m, ref["master"], t + " master")
+            rms = float(np.sqrt(np.mean(ref["master"].astype(np.float64) ** 2)))
+            bits = PU.bits_of(st.get_version(j, slot))
+            PU.assert_bf16_within_one_ulp(bits, ref["new"], t + " version", abs_slack=PU.RTOL * rms)
+            PU.assert_bf16_is_rounded_master(bits, got_m, t + " version vs own master")
+        else:
+            PU.assert_close_f32(st.get_version(j, slot).numpy(), ref["new"], t + " version")
+        np.testing.assert_allclose(norms[j], ref["norms"], rtol=PU.RTOL, atol=1e-30, err_msg=t + " norms")
+        new_state.append((got_r.copy(), got_a.copy()))
+        new_lams.append(float(lam_gpu[j]))
+    return new_state, new_lams
+
+
+@pytest.mark.parametrize("precision", ["f32", "bf16"])
+@pytest.mark.parametrize("K", [-1, 2, 1])
+def test_one_adaptive_step(precision, K):
+    w = W.custom_workload("adaptive", [[50_000, 24], [33_001], [20_000], [8_192]], [5, 3, 1, 0], 6, K,
+                          precision=precision, seed=31, lam=0.4)
+    plan, st, host = PU.load_workload(w, amplified=True)
+    state = _state(w, st, 31, w.lam)
+    alpha, eta_l = 0.9, 1e-3
+    st.step_adaptive(alpha, eta_l, w.lr)
+    torch.cuda.synchronize()
+    _, lams = _check(w, plan, st, host, state, [w.lam] * 4, alpha, eta_l, K, f"K={K}")
+    assert abs(lams[0] - w.lam) > 1e-3           # lambda really moved
+    assert lams[3] == np.float32(w.lam)          # the stage without staleness is left alone
+
+
+def test_adaptive_trajectory_over_several_steps():
+    tau = [2, 1, 0]
+    w = W.custom_workload("adaptive_steps", [[30_000], [12_345], [4_096]], tau, 3, -1, seed=32, lam=0.2)
+    plan, st, host = PU.load_workload(w, amplified=True)
+    st.enable_adaptive(w.lam)                    # the paper's start: lambda = lambda0, v_r = v_a = 0
+    state = [(np.zeros(n, np.float32), np.zeros(n, np.float32)) for n in w.stage_numel()]
+    lams = [w.lam] * 3
+    alpha, eta_l = 0.5, 2e-3
+    for step in range(6):
+        for j in range(3):
+            g = W.draw_grads(w, j, w.stage_numel()[j], amplified=True, step=step)
+            st.set_flat(st.grads, j, g)
+            host[j].grads = g
+        st.step_adaptive(alpha, eta_l, w.lr)
+        torch.cuda.synchronize()
+        state, lams = _check(w, plan, st, host, state, lams, alpha, eta_l, -1, f"step {step}")
+        # adopt the device's new version on the host side, then commit
+        for j in range(3):
+            new = st.get_version(j, plan.stage_write_slot(j))
+            host[j].versions = host[j].versions[1:] + [new]
+        st.commit()
+    assert lams[0] != np.float32(w.lam) and lams[2] == np.float32(w.lam)
+
+
+def test_zero_eta_lambda_is_the_fixed_lambda_step():
+    w = W.custom_workload("adaptive_off", [[40_000], [10_000]], [3, 1], 5, -1, seed=33, lam=0.3)   # depth > tau+1: re-running a step is idempotent
+    plan, st, host = PU.load_workload(w, amplified=True)
+    st.step(w.lam, w.lr)
+    torch.cuda.synchronize()
+    want = [st.get_version(j, plan.stage_write_slot(j)) for j in range(2)]
+    want_g = [st.get_flat(st.grad_out, j) for j in range(2)]
+    state = _state(w, st, 33, w.lam)
+    st.step_adaptive(0.9, 0.0, w.lr)
+    torch.cuda.synchronize()
+    for j in range(2):
+        assert torch.equal(st.get_version(j, plan.stage_write_slot(j)), want[j])
+        assert torch.equal(st.get_flat(st.grad_out, j), want_g[j])
+        assert np.array_equal(st.get_flat(st.v_r, j).numpy(), state[j][0])
+        assert np.array_equal(st.get_flat(st.v_a, j).numpy(), state[j][1])
+    assert torch.equal(st.lambda_dev.cpu(), torch.full((2,), w.lam))
+
+
+def test_adaptive_step_at_benchmark_shape():
+    """ViT-B-sized workload, the launch configuration bench.py --adaptive times."""
+    w = W.make_workload(4)
+    plan, st, host = PU.load_workload(w, amplified=True)
+    state = _state(w, st, 34, w.lam)
+    st.step_adaptive(0.9, 1e-5, w.lr)
+    torch.cuda.synchronize()
+    _check(w, plan, st, host, state, [w.lam] * w.n_stages, 0.9, 1e-5, w.n_iters, "vit")

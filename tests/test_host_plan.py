@@ -230,3 +230,24 @@ def test_queries_on_null_or_out_of_range(lib):
     plan, _ = _plan([[64]], [0], R=1)
     assert plan.stage_numel(3) == -1 and plan.tensor_offset(-1) == -1
     lib.ferret_plan_destroy(None)
+
+
+def test_adaptive_step_argument_errors(lib):
+    plan, _ = _plan([[64]], [1], R=2)
+    plan.set_state([0], [1])
+    fn = lib.ferret_compensate_step_adaptive
+    ad = B.ferret_adaptive(16, 16, 16, 0.9, 1e-3)
+    import ctypes
+    assert fn(plan.handle, 16, 16, None, None, 0.01, None, None, 16, None) == B.FERRET_EINVAL      # no state
+    assert fn(plan.handle, 16, 16, None, ctypes.byref(ad), 0.01, None, None, None, None) == B.FERRET_EINVAL  # no workspace
+    bad = B.ferret_adaptive(16, 16, 16, 1.0, 1e-3)
+    assert fn(plan.handle, 16, 16, None, ctypes.byref(bad), 0.01, None, None, 16, None) == B.FERRET_EINVAL
+    assert "alpha" in B.last_error()
+    bad = B.ferret_adaptive(16, 24, 16, 0.9, 1e-3)
+    assert fn(plan.handle, 16, 16, None, ctypes.byref(bad), 0.01, None, None, 16, None) == B.FERRET_EINVAL
+    bad = B.ferret_adaptive(16, 16, 16, 0.9, -1.0)
+    assert fn(plan.handle, 16, 16, None, ctypes.byref(bad), 0.01, None, None, 16, None) == B.FERRET_EINVAL
+    zero, _ = _plan([[64]], [1], K=0, R=2)
+    zero.set_state([0], [1])
+    assert fn(zero.handle, 16, 16, None, ctypes.byref(ad), 0.01, None, None, 16, None) == B.FERRET_EINVAL
+    assert "n_iters" in B.last_error()
