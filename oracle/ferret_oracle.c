@@ -241,3 +241,52 @@ double ferret_oracle_lambda_update(int64_t n, const void *g0, const void *V0, co
     if (sums) { sums[0] = dot_a_dr; sums[1] = dot_a_a; }
     return lambda_new;
 }
+
+/* ==== gradient accumulation (T2 of Sec. "Fine-grained Pipeline Parallelism") ==============
+ *
+ * With c^a accumulation steps a stage applies one update per c^a gradients, which is why it
+ * only has to keep 1 + ceil((P-j-1)/c^a) versions.  The paper does not say how compensation
+ * and accumulation compose; the reading used here: every arriving gradient is first
+ * compensated from the version it was taken on to the stage's CURRENT version (Alg. 1's
+ * iterations, with that gradient's own staleness tau, counted in stored versions), then added
+ * to the running sum; the arrival that completes the group applies
+ *     theta_next = V[tau] - eta * scale * (sum of the compensated gradients)
+ * and clears the sum.  scale is 1 for a plain sum, 1/c^a for a mean.  With c^a = 1 (sum empty
+ * on entry, scale 1) this is Alg. 1 itself.
+ *
+ * accum_in / accum_out  fp32[n] (may alias)
+ * do_update             0: accumulate only (theta_new, master_new untouched)
+ *                       1: accumulate, update, clear the sum
+ * bf16                  storage type of V, g0, theta_new (uint16 bit patterns) vs fp32;
+ *                       with bf16 the update goes to the fp32 master (master, master_new)
+ */
+int ferret_oracle_accumulate(int64_t n, int32_t n_versions, const void *const *V, const void *g0,
+                             int32_t bf16, const float *master, int32_t K, double lambda, double eta,
+                             double scale, int32_t do_update, const float *accum_in, float *accum_out,
+                             void *theta_new, float *master_new, double *g_out)
+{
+    if (n < 0 || n_versions < 1 || n_versions > FERRET_ORACLE_MAX_VERSIONS) return -1;
+    const int32_t tau = n_versions - 1;
+    const int32_t Kp = ferret_oracle_effective_iters(K, tau);
+    for (int64_t e = 0; e < n; ++e) {
+        double v[FERRET_ORACLE_MAX_VERSIONS];
+        for (int32_t s = 0; s <= tau; ++s) v[s] = widen_at(V[s], e, bf16);
+        double g = compensate_one(widen_at(g0, e, bf16), v, tau, Kp, lambda);
+        double total = (double)accum_in[e] + g;
+        if (g_out) g_out[e] = g;
+        if (!do_update) {
+            accum_out[e] = (float)total;
+            continue;
+        }
+        double base = bf16 ? (double)master[e] : v[tau];
+        float updated = (float)(base - eta * scale * total);
+        if (bf16) {
+            master_new[e] = updated;
+            ((uint16_t *)theta_new)[e] = ferret_oracle_f32_to_bf16(updated);
+        } else {
+            ((float *)theta_new)[e] = updated;
+        }
+        accum_out[e] = 0.0f;
+    }
+    return 0;
+}

@@ -65,6 +65,11 @@ def _load():
             ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32,
             ctypes.c_double, ctypes.c_double, ctypes.c_double, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+        lib.ferret_oracle_accumulate.restype = ctypes.c_int
+        lib.ferret_oracle_accumulate.argtypes = [
+            ctypes.c_int64, ctypes.c_int32, pp, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32,
+            ctypes.c_double, ctypes.c_double, ctypes.c_double, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
         _lib = lib
     return _lib
 
@@ -194,6 +199,36 @@ def compensate_stage_adaptive(versions, g0, master, K: int, lam: float, alpha: f
     else:
         new, g_out, norms = compensate_stage_f32(versions, g0, K, lam_new, eta, n_threads)
         out.update(new=new, g=g_out, norms=norms)
+    return out
+
+
+# ---- gradient accumulation (T2) --------------------------------------------------------------
+def accumulate_stage(versions, g0, master, K: int, lam: float, eta: float, scale: float, do_update: bool,
+                     accum, bf16: bool = False):
+    """Compensate one arriving gradient to the current version, add it to the running sum and, when
+    do_update, apply theta_next = V[tau] - eta*scale*sum and clear the sum.
+    Returns dict(accum=float32[n], g=float64[n], new=..., master=...) (new/master only when do_update)."""
+    dt = np.uint16 if bf16 else np.float32
+    V = [_as_np(v, dt) for v in versions]
+    g = _as_np(g0, dt)
+    acc = _as_np(accum, np.float32)
+    n = g.size
+    m = _as_np(master, np.float32) if bf16 else None
+    acc_out = np.empty(n, np.float32)
+    g_out = np.empty(n, np.float64)
+    new = np.zeros(n, dt)
+    m_new = np.zeros(n, np.float32) if bf16 else None
+    rc = _load().ferret_oracle_accumulate(
+        n, len(V), _ptr_array(V), g.ctypes.data, int(bf16), m.ctypes.data if bf16 else None, K, float(lam),
+        float(eta), float(scale), int(bool(do_update)), acc.ctypes.data, acc_out.ctypes.data, new.ctypes.data,
+        m_new.ctypes.data if bf16 else None, g_out.ctypes.data)
+    if rc != 0:
+        raise ValueError("ferret_oracle_accumulate: bad arguments")
+    out = dict(accum=acc_out, g=g_out)
+    if do_update:
+        out["new"] = new
+        if bf16:
+            out["master"] = m_new
     return out
 
 

@@ -405,7 +405,11 @@ __device__ __forceinline__ void process_chunk(const StepArgs &a, const ChunkInfo
                                               float (&red)[3][kWaves]) {
     float acc[3] = {0.f, 0.f, 0.f};
     // the coefficient: one scalar for the call, or this stage's self-tuned one from device memory
-    const float lambda = a.lambda_dev ? a.lambda_dev[c.stage] : a.lambda;
+    // (read through the constant address space: a scalar load; the array was last written by an
+    // earlier kernel of the same stream)
+    typedef const float __attribute__((address_space(4))) *const_f32_ptr;
+    const float lambda = a.lambda_dev ? *reinterpret_cast<const_f32_ptr>(reinterpret_cast<uintptr_t>(a.lambda_dev + c.stage))
+                                      : a.lambda;
     // versions to read: the K'+1 boundaries; with K' = 0 only V[tau], plus V[0] when the weight
     // gap is wanted for the norms
     if (c.kp == 0) {
