@@ -98,6 +98,8 @@ def main():
     ap.add_argument("--iters", type=int, default=None, help="override K (-1 = one iteration per version step)")
     ap.add_argument("--adaptive", action="store_true",
                     help="time the self-tuned-lambda step (all of Alg. 1) instead of the fixed-lambda step")
+    ap.add_argument("--accumulate", type=int, default=0, metavar="CA",
+                    help="time gradient accumulation (T2): one step = CA arrivals per stage, the last one updates")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="do not record per-launch HIP events (roofline is then taken from wall time)")
     args = ap.parse_args()
@@ -152,7 +154,25 @@ def main():
         step_bytes += state_bytes
         log(f"adaptive lambda: state pass adds {state_bytes} algorithmic bytes per step")
 
+    accum = None
+    if args.accumulate:
+        ca = args.accumulate
+        accum = torch.zeros(plan.flat_elems, dtype=torch.float32, device=dev)
+        elt = 4 if w.precision == "f32" else 2
+        per_arrival = sum((elt * (plan.stage_effective_iters(j) + 2) + 8) * n for j, n in enumerate(w.stage_numel()))
+        last_extra = sum((elt + (8 if w.precision == "bf16" else 0)) * n for n in w.stage_numel())
+        step_bytes = ca * per_arrival + last_extra
+        log(f"accumulation: {ca} arrivals per step, algorithmic bytes per step {step_bytes}")
+
     def one_step():
+        if args.accumulate:
+            for k in range(args.accumulate):
+                last = k == args.accumulate - 1
+                B.ferret_accumulate_step(plan, st.ring, st.grads, st.master, accum, 1.0 / args.accumulate,
+                                         [2 if last else 1] * w.n_stages, None, w.lam, w.lr,
+                                         st.norms if norms else None, None, st.workspace if norms else None)
+            st.commit()
+            return
         if args.adaptive:
             st.step_adaptive(0.9, 2e-6, w.lr, norms=norms, grad_out=False)
         else:
@@ -164,20 +184,22 @@ def main():
     torch.cuda.synchronize()
 
     if not args.no_kernel_events:
-        B.ferret_profile_begin(args.steps)
+        B.ferret_profile_begin(args.steps * max(args.accumulate, 1))
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
         one_step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    kernel_ms = B.ferret_profile_end(args.steps) if not args.no_kernel_events else [elapsed * 1e3 / args.steps]
+    n_launch = args.steps * max(args.accumulate, 1)
+    kernel_ms = B.ferret_profile_end(n_launch) if not args.no_kernel_events else [elapsed * 1e3 / args.steps]
 
     ms_per_step = elapsed * 1e3 / args.steps
     params_per_s = w.numel / (elapsed / args.steps)
     k_avg = statistics.fmean(kernel_ms)
     k_med = statistics.median(kernel_ms)
-    achieved = plan.step_bytes / (k_avg * 1e-3) / 1e9      # the fused step kernel alone
+    per_launch_bytes = step_bytes / args.accumulate if args.accumulate else plan.step_bytes
+    achieved = per_launch_bytes / (k_avg * 1e-3) / 1e9     # the fused step kernel alone
     log(f"step: {ms_per_step * 1e3:.1f} us wall per step; fused kernel avg {k_avg * 1e3:.1f} us, median "
         f"{k_med * 1e3:.1f} us, min {min(kernel_ms) * 1e3:.1f} us -> {achieved:.0f} GB/s algorithmic "
         f"({achieved / HBM_PEAK_GBS:.1%} of {HBM_PEAK_GBS:.0f} GB/s)")
@@ -212,7 +234,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "params": w.numel, "stages": w.n_stages, "staleness": w.staleness,
                    "ring_depth": w.ring_depth, "n_iters": w.n_iters, "lambda": w.lam, "lr": w.lr,
-                   "norms": norms, "adaptive_lambda": bool(args.adaptive), "chunk_elems": plan.chunk_elems,
+                   "norms": norms, "adaptive_lambda": bool(args.adaptive), "accumulation_steps": args.accumulate,
+                   "chunk_elems": plan.chunk_elems,
                    "algorithmic_bytes_per_step": step_bytes},
         "hbm_gbs_wall": step_bytes / (elapsed / args.steps) / 1e9,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",

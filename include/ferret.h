@@ -236,6 +236,34 @@ ferret_status ferret_compensate_step_adaptive(const ferret_plan *plan, void *rin
                                               float *norms_out, void *grad_out, void *workspace,
                                               void *hip_stream);
 
+/* ---- gradient accumulation (T2) -------------------------------------------------------------- */
+/* Sec. "Fine-grained Pipeline Parallelism", T2: with c^a accumulation steps a stage applies one
+ * update per c^a gradients and therefore keeps only 1 + ceil((P-j-1)/c^a) versions (plan the ring
+ * with tau_j = ceil((P-j-1)/c^a) and FERRET_RING_DEPTH_MINIMAL).  The paper does not say how
+ * compensation and accumulation compose; here every arriving gradient is compensated from the
+ * version it was taken on to the stage's current version, then added to a running sum, and the
+ * arrival that completes the group applies  theta_next = V[tau] - eta * scale * sum  and clears the
+ * sum.  One call handles one arrival per participating stage:
+ *   accum      device fp32 flat buffer, the running sums; zero it before the first arrival
+ *   scale      1 for a sum of gradients, 1/c^a for their mean
+ *   mode       host int32[n_stages]: 0 = stage takes no part in this call, 1 = accumulate only,
+ *              2 = accumulate, update (new version into slot head+1) and clear the sum
+ *   staleness  host int32[n_stages] or NULL: staleness of THIS gradient in stored versions,
+ *              0 .. tau_j (it varies from arrival to arrival when c^a does not divide P-j-1);
+ *              NULL = the plan's tau_j
+ * Other arguments as in ferret_compensate_step; norms_out rows of skipped stages read 0.  Commit
+ * the stages that were updated with ferret_push_version(.., stage, src = NULL). */
+typedef struct {
+    float *accum;
+    float scale;
+    const int32_t *mode;
+    const int32_t *staleness;
+} ferret_accumulate;
+
+ferret_status ferret_accumulate_step(const ferret_plan *plan, void *ring, const void *grads, float *master,
+                                     const ferret_accumulate *accumulate, float lambda, float lr,
+                                     float *norms_out, void *grad_out, void *workspace, void *hip_stream);
+
 /* ---- misc ------------------------------------------------------------------------------------ */
 const char *ferret_last_error(void);   /* message of the calling thread's last failed call */
 const char *ferret_version(void);

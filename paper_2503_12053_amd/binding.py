@@ -46,6 +46,11 @@ class ferret_adaptive(ctypes.Structure):
                 ("eta_lambda", c_float)]
 
 
+class ferret_accumulate(ctypes.Structure):
+    _fields_ = [("accum", c_void_p), ("scale", c_float), ("mode", POINTER(c_int32)),
+                ("staleness", POINTER(c_int32))]
+
+
 class FerretError(RuntimeError):
     def __init__(self, status: int, message: str):
         super().__init__(f"{STATUS_NAMES.get(status, status)}: {message}")
@@ -93,6 +98,7 @@ SIGNATURES = {
     "ferret_push_version": (c_int32, [_P, _P, _P, c_int32, _P, _P]),
     "ferret_compensate_step": (c_int32, [_P, _P, _P, _P, c_float, c_float, _P, _P, _P, _P]),
     "ferret_compensate_step_adaptive": (c_int32, [_P, _P, _P, _P, POINTER(ferret_adaptive), c_float, _P, _P, _P, _P]),
+    "ferret_accumulate_step": (c_int32, [_P, _P, _P, _P, POINTER(ferret_accumulate), c_float, c_float, _P, _P, _P, _P]),
     "ferret_last_error": (c_char_p, []),
     "ferret_version": (c_char_p, []),
     "ferret_copy_bytes": (c_int32, [_P, _P, c_size_t, _P]),
@@ -187,6 +193,17 @@ def ferret_compensate_step_adaptive(plan: "Plan", ring, grads, master, lambda_de
     _check(load().ferret_compensate_step_adaptive(plan.handle, _ptr(ring), _ptr(grads), _ptr(master), byref(ad), lr,
                                                   _ptr(norms_out), _ptr(grad_out), _ptr(workspace),
                                                   _stream(stream)))
+
+
+def ferret_accumulate_step(plan: "Plan", ring, grads, master, accum, scale: float, mode: Sequence[int],
+                           staleness: Optional[Sequence[int]], lam: float, lr: float, norms_out=None,
+                           grad_out=None, workspace=None, stream=None) -> None:
+    P = plan.n_stages
+    mode_arr = (c_int32 * P)(*[int(m) for m in mode])
+    st_arr = (c_int32 * P)(*[int(x) for x in staleness]) if staleness is not None else None
+    acc = ferret_accumulate(_ptr(accum), scale, mode_arr, st_arr)
+    _check(load().ferret_accumulate_step(plan.handle, _ptr(ring), _ptr(grads), _ptr(master), byref(acc), lam, lr,
+                                         _ptr(norms_out), _ptr(grad_out), _ptr(workspace), _stream(stream)))
 
 
 def ferret_copy_bytes(dst, src, n_bytes: int, stream=None) -> None:

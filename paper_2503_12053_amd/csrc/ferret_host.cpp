@@ -445,6 +445,43 @@ ferret_status ferret_compensate_step_adaptive(const ferret_plan *plan, void *rin
     return FERRET_OK;
 }
 
+ferret_status ferret_accumulate_step(const ferret_plan *plan, void *ring, const void *grads, float *master,
+                                     const ferret_accumulate *acc, float lambda, float lr, float *norms_out,
+                                     void *grad_out, void *workspace, void *hip_stream) {
+    const char *who = "accumulate_step";
+    ferret_status rc = check_step_args(who, plan, ring, grads, master, norms_out, grad_out, workspace);
+    if (rc != FERRET_OK) return rc;
+    if (!acc || !acc->accum || !acc->mode) { set_error("%s: null accumulate, accum or mode", who); return FERRET_EINVAL; }
+    if (!aligned16(acc->accum)) { set_error("%s: accum must be 16-byte aligned", who); return FERRET_EINVAL; }
+    const size_t P = plan->stages.size();
+    for (size_t j = 0; j < P; ++j) {
+        if (acc->mode[j] < 0 || acc->mode[j] > 2) { set_error("%s: mode[%zu] = %d, need 0..2", who, j, acc->mode[j]); return FERRET_EINVAL; }
+        if (acc->staleness && (acc->staleness[j] < 0 || acc->staleness[j] > plan->stages[j].tau)) {
+            set_error("%s: staleness[%zu] = %d, need 0..%d (the plan's tau)", who, j, acc->staleness[j],
+                      plan->stages[j].tau);
+            return FERRET_EINVAL;
+        }
+    }
+    StepArgs a;
+    fill_step_args(plan, a, ring, grads, master, lambda, lr, norms_out, grad_out, workspace);
+    a.accum = acc->accum;
+    a.accum_scale = acc->scale;
+    for (size_t j = 0; j < P; ++j) {
+        a.mode[j] = (uint8_t)acc->mode[j];
+        if (acc->staleness) {
+            const int32_t have = effective_tau(plan->stages[j]);
+            const int32_t tau = acc->staleness[j] < have ? acc->staleness[j] : have;
+            a.stage[j].tau = (uint16_t)tau;
+            a.stage[j].kp = (uint16_t)effective_iters(plan->n_iters, tau);
+        }
+    }
+    int err = launch_step(*plan, a, norms_out, hip_stream);
+    if (err) { set_error("%s: launch failed: %s", who, device_error_string(err)); return FERRET_EDEVICE; }
+    for (size_t j = 0; j < P; ++j)
+        if (acc->mode[j] == 2) plan->stages[j].step_pending = true;
+    return FERRET_OK;
+}
+
 ferret_status ferret_copy_bytes(void *dst, const void *src, size_t n_bytes, void *hip_stream) {
     if (!dst || !src || !aligned16(dst) || !aligned16(src) || (n_bytes & 15u)) {
         set_error("copy_bytes: need non-null 16-byte aligned pointers and a multiple of 16 bytes");

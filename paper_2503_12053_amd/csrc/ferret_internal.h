@@ -52,6 +52,11 @@ struct StepArgs {
     float *v_a;
     float alpha;
     float eta_lambda;
+    // gradient accumulation (null for the plain step)
+    float *accum;        // fp32 flat buffer: running sum of compensated gradients
+    float accum_scale;   // factor on the sum at the update
+    uint32_t pad2_;
+    uint8_t mode[FERRET_MAX_STAGES];   // per stage: 0 skip, 1 accumulate only, 2 accumulate + update
     // chunk_begin of every stage again, densely packed (unused entries = UINT32_MAX), so that a
     // workgroup can find its chunk's stage with a few wide scalar loads
     uint32_t chunk_begin[FERRET_MAX_STAGES];

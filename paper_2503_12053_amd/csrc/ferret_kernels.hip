@@ -154,6 +154,9 @@ struct ChunkPtrs {
     char *out;                      // slot of the new version
     char *master;                   // fp32 master (bf16 storage only)
     char *g_out;                    // fp32 compensated gradient, nullable
+    char *accum;                    // fp32 running sum of compensated gradients (accumulation kernels)
+    float acc_scale;                // factor applied to the sum at the update
+    bool acc_update;                // this arrival completes the group: update and clear the sum
 };
 
 template <typename T>
@@ -166,47 +169,76 @@ __device__ __forceinline__ void st_off(char *base, uint32_t byte_off, const T &v
 }
 
 template <typename S>
-__device__ __forceinline__ void load_master(const char *master, uint32_t vec, v4f (&m)[S::kF4]) {
-    if (S::kMaster) {
+__device__ __forceinline__ void load_master(const char *master, uint32_t vec, v4f (&m)[S::kF4], bool needed = true) {
+    if (S::kMaster && needed) {
 #pragma unroll
         for (int q = 0; q < S::kF4; ++q) m[q] = ld_off<v4f>(master, vec * (uint32_t)(S::kElems * 4) + 16u * q);
     }
 }
 
+template <typename S, int OUT>
+__device__ __forceinline__ void load_accum(const char *accum, uint32_t vec, v4f (&ac)[S::kF4]) {
+    if (OUT & 2) {
+#pragma unroll
+        for (int q = 0; q < S::kF4; ++q) ac[q] = ld_off<v4f>(accum, vec * (uint32_t)(S::kElems * 4) + 16u * q);
+    }
+}
+
 // theta_next = V[tau] - eta * g (fp32 storage), or master - eta * g with the stored version its
 // round-to-nearest-even bf16; then the stores of one lane-vector.
-template <typename S, int NV, bool GOUT>
+template <typename S, int NV, int OUT>
 __device__ __forceinline__ void update_and_store(const ChunkPtrs<NV> &p, uint32_t vec, const float (&g)[S::kElems],
                                                  const float (&newest)[S::kElems], const v4f (&m_in)[S::kF4],
-                                                 float lr) {
+                                                 const v4f (&ac_in)[S::kF4], float lr) {
     constexpr int E = S::kElems;
     constexpr uint32_t kF32Bytes = E * 4;
-    float w[E];
-    if (S::kMaster) {
-#pragma unroll
-        for (int q = 0; q < S::kF4; ++q) {
-            w[4 * q + 0] = fmaf(-lr, g[4 * q + 0], m_in[q].x); w[4 * q + 1] = fmaf(-lr, g[4 * q + 1], m_in[q].y);
-            w[4 * q + 2] = fmaf(-lr, g[4 * q + 2], m_in[q].z); w[4 * q + 3] = fmaf(-lr, g[4 * q + 3], m_in[q].w);
-            st_off(p.master, vec * kF32Bytes + 16u * q, make_v4f(w[4 * q], w[4 * q + 1], w[4 * q + 2], w[4 * q + 3]));
-        }
-    } else {
-#pragma unroll
-        for (int e = 0; e < E; ++e) w[e] = fmaf(-lr, g[e], newest[e]);
-    }
-    st_off(p.out, vec * (uint32_t)S::kRawBytes, S::narrow(w));
-    if (GOUT) {
+    if (OUT & 1) {
 #pragma unroll
         for (int q = 0; q < S::kF4; ++q)
             st_off(p.g_out, vec * kF32Bytes + 16u * q, make_v4f(g[4 * q], g[4 * q + 1], g[4 * q + 2], g[4 * q + 3]));
     }
+    float step[E];          // what the update subtracts eta times: g, or scale * (running sum + g)
+#pragma unroll
+    for (int e = 0; e < E; ++e) step[e] = g[e];
+    if (OUT & 2) {          // gradient accumulation: add this compensated gradient to the running sum
+#pragma unroll
+        for (int q = 0; q < S::kF4; ++q) {
+            step[4 * q + 0] += ac_in[q].x; step[4 * q + 1] += ac_in[q].y;
+            step[4 * q + 2] += ac_in[q].z; step[4 * q + 3] += ac_in[q].w;
+        }
+        if (!p.acc_update) {        // uniform: not the last arrival of the group, only the sum moves
+#pragma unroll
+            for (int q = 0; q < S::kF4; ++q)
+                st_off(p.accum, vec * kF32Bytes + 16u * q,
+                       make_v4f(step[4 * q], step[4 * q + 1], step[4 * q + 2], step[4 * q + 3]));
+            return;
+        }
+#pragma unroll
+        for (int q = 0; q < S::kF4; ++q) st_off(p.accum, vec * kF32Bytes + 16u * q, make_v4f(0.f, 0.f, 0.f, 0.f));
+#pragma unroll
+        for (int e = 0; e < E; ++e) step[e] *= p.acc_scale;
+    }
+    float w[E];
+    if (S::kMaster) {
+#pragma unroll
+        for (int q = 0; q < S::kF4; ++q) {
+            w[4 * q + 0] = fmaf(-lr, step[4 * q + 0], m_in[q].x); w[4 * q + 1] = fmaf(-lr, step[4 * q + 1], m_in[q].y);
+            w[4 * q + 2] = fmaf(-lr, step[4 * q + 2], m_in[q].z); w[4 * q + 3] = fmaf(-lr, step[4 * q + 3], m_in[q].w);
+            st_off(p.master, vec * kF32Bytes + 16u * q, make_v4f(w[4 * q], w[4 * q + 1], w[4 * q + 2], w[4 * q + 3]));
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < E; ++e) w[e] = fmaf(-lr, step[e], newest[e]);
+    }
+    st_off(p.out, vec * (uint32_t)S::kRawBytes, S::narrow(w));
 }
 
 // Finish one vector: iterate, update, store.  raw_g / raw_v hold the loaded inputs.
-template <typename S, int NV, bool COMP, bool NORMS, bool GOUT>
+template <typename S, int NV, bool COMP, bool NORMS, int OUT>
 __device__ __forceinline__ void finish_vector(const ChunkPtrs<NV> &p, uint32_t vec,
                                               const typename S::Raw &raw_g,
                                               const typename S::Raw (&raw_v)[NV], const v4f (&m_in)[S::kF4],
-                                              float lambda, float lr, float (&acc)[3]) {
+                                              const v4f (&ac_in)[S::kF4], float lambda, float lr, float (&acc)[3]) {
     constexpr int E = S::kElems;
     float g[E], prev[E], cur[E], first[E];
     S::widen(raw_g, g);
@@ -234,7 +266,7 @@ __device__ __forceinline__ void finish_vector(const ChunkPtrs<NV> &p, uint32_t v
             acc[2] = fmaf(gap, gap, acc[2]);
         }
     }
-    update_and_store<S, NV, GOUT>(p, vec, g, prev, m_in, lr);
+    update_and_store<S, NV, OUT>(p, vec, g, prev, m_in, ac_in, lr);
 }
 
 // A chunk with a compile-time number NV of versions to read.  Groups of kThreads*kUnroll vectors
@@ -242,7 +274,7 @@ __device__ __forceinline__ void finish_vector(const ChunkPtrs<NV> &p, uint32_t v
 // predicated vector at a time.  Within a group all loads come first and all stores last, which
 // is also what makes the in-place case (new version written over the oldest one read) safe:
 // each vector is read and written by the same lane.
-template <typename S, int NV, bool COMP, bool NORMS, bool GOUT>
+template <typename S, int NV, bool COMP, bool NORMS, int OUT>
 __device__ __forceinline__ void run_chunk(const ChunkPtrs<NV> &p, uint32_t n_vecs, float lambda,
                                           float lr, float (&acc)[3]) {
     using Raw = typename S::Raw;
@@ -253,7 +285,7 @@ __device__ __forceinline__ void run_chunk(const ChunkPtrs<NV> &p, uint32_t n_vec
 
     for (uint32_t base = 0; base < n_grouped; base += group) {
         Raw rg[kUnroll], rv[kUnroll][NV];
-        v4f m[kUnroll][S::kF4];
+        v4f m[kUnroll][S::kF4], ac[kUnroll][S::kF4];
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) rg[u] = ld_off<Raw>(p.g, (base + u * kThreads + tid) * RB);
 #pragma unroll
@@ -261,25 +293,29 @@ __device__ __forceinline__ void run_chunk(const ChunkPtrs<NV> &p, uint32_t n_vec
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) rv[u][s] = ld_off<Raw>(p.v[s], (base + u * kThreads + tid) * RB);
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) load_master<S>(p.master, base + u * kThreads + tid, m[u]);
+        for (int u = 0; u < kUnroll; ++u) {
+            load_master<S>(p.master, base + u * kThreads + tid, m[u], !(OUT & 2) || p.acc_update);
+            load_accum<S, OUT>(p.accum, base + u * kThreads + tid, ac[u]);
+        }
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u)
-            finish_vector<S, NV, COMP, NORMS, GOUT>(p, base + u * kThreads + tid, rg[u], rv[u], m[u], lambda,
-                                                    lr, acc);
+            finish_vector<S, NV, COMP, NORMS, OUT>(p, base + u * kThreads + tid, rg[u], rv[u], m[u], ac[u], lambda,
+                                                   lr, acc);
     }
     for (uint32_t vec = n_grouped + tid; vec < n_vecs; vec += kThreads) {
         Raw rg = ld_off<Raw>(p.g, vec * RB), rv[NV];
-        v4f m[S::kF4];
+        v4f m[S::kF4], ac[S::kF4];
 #pragma unroll
         for (int s = 0; s < NV; ++s) rv[s] = ld_off<Raw>(p.v[s], vec * RB);
-        load_master<S>(p.master, vec, m);
-        finish_vector<S, NV, COMP, NORMS, GOUT>(p, vec, rg, rv, m, lambda, lr, acc);
+        load_master<S>(p.master, vec, m, !(OUT & 2) || p.acc_update);
+        load_accum<S, OUT>(p.accum, vec, ac);
+        finish_vector<S, NV, COMP, NORMS, OUT>(p, vec, rg, rv, m, ac, lambda, lr, acc);
     }
 }
 
 // Any number of versions (K' > 8): stream them, four boundaries at a time.  `arena` points at this
 // chunk's first element in slot 0 of the stage; slots are slot_bytes apart.
-template <typename S, bool NORMS, bool GOUT>
+template <typename S, bool NORMS, int OUT>
 __device__ __forceinline__ void run_chunk_streamed(const ChunkPtrs<1> &p, const char *arena, uint64_t slot_bytes,
                                                    uint32_t R, uint32_t head, uint32_t tau, uint32_t kp,
                                                    uint32_t n_vecs, float lambda, float lr, float (&acc)[3]) {
@@ -289,10 +325,11 @@ __device__ __forceinline__ void run_chunk_streamed(const ChunkPtrs<1> &p, const 
     const uint32_t oldest = (head + R - tau) % R;
     for (uint32_t vec = threadIdx.x; vec < n_vecs; vec += kThreads) {
         float g[E], prev[E], cur[E], first[E];
-        v4f m[S::kF4];
+        v4f m[S::kF4], ac[S::kF4];
         Raw rg = ld_off<Raw>(p.g, vec * RB);
         Raw r0 = ld_off<Raw>(arena + (uint64_t)oldest * slot_bytes, vec * RB);
-        load_master<S>(p.master, vec, m);
+        load_master<S>(p.master, vec, m, !(OUT & 2) || p.acc_update);
+        load_accum<S, OUT>(p.accum, vec, ac);
         S::widen(rg, g);
         S::widen(r0, prev);
 #pragma unroll
@@ -337,7 +374,7 @@ __device__ __forceinline__ void run_chunk_streamed(const ChunkPtrs<1> &p, const 
                 acc[2] = fmaf(gap, gap, acc[2]);
             }
         }
-        update_and_store<S, 1, GOUT>(p, vec, g, prev, m, lr);
+        update_and_store<S, 1, OUT>(p, vec, g, prev, m, ac, lr);
     }
 }
 
@@ -356,6 +393,8 @@ struct ChunkInfo {
     uint32_t n_vecs;         // 16-byte storage vectors in the chunk
     uint32_t R, head, tau, kp;
     uint32_t stage;
+    bool acc_update;         // accumulation kernels: this call updates the stage
+    bool skip;               // accumulation kernels: the stage takes no part in this call
 };
 
 template <typename S>
@@ -375,11 +414,14 @@ __device__ __forceinline__ ChunkInfo chunk_info(const StepArgs &a, const StageDe
     c.arena = static_cast<const char *>(a.ring) + (uniform(d.ring_base) + e0) * kStoreBytes;
     c.flat_elem0 = uniform(d.flat_off) + e0;
     c.stage = stage;
+    const uint32_t mode = a.accum ? a.mode[stage] : 2u;     // 0 skip, 1 accumulate, 2 accumulate + update
+    c.acc_update = mode == 2u;
+    c.skip = mode == 0u;
     return c;
 }
 
 // Fixed-NV dispatch target: builds the chunk's pointers.
-template <typename S, int NV, bool COMP, bool NORMS, bool GOUT>
+template <typename S, int NV, bool COMP, bool NORMS, int OUT>
 __device__ __forceinline__ void do_chunk(const StepArgs &a, const ChunkInfo &c, float lambda, float (&acc)[3]) {
     constexpr uint64_t kStoreBytes = S::kStoreBytes;
     ChunkPtrs<NV> p;
@@ -394,16 +436,23 @@ __device__ __forceinline__ void do_chunk(const StepArgs &a, const ChunkInfo &c, 
     }
     p.out = const_cast<char *>(c.arena) + (uint64_t)((c.head + 1) % c.R) * c.slot_bytes;
     p.master = a.master ? reinterpret_cast<char *>(a.master) + c.flat_elem0 * 4 : nullptr;
-    p.g_out = GOUT ? reinterpret_cast<char *>(a.grad_out) + c.flat_elem0 * 4 : nullptr;
-    run_chunk<S, NV, COMP, NORMS, GOUT>(p, c.n_vecs, lambda, a.lr, acc);
+    p.g_out = (OUT & 1) ? reinterpret_cast<char *>(a.grad_out) + c.flat_elem0 * 4 : nullptr;
+    p.accum = (OUT & 2) ? reinterpret_cast<char *>(a.accum) + c.flat_elem0 * 4 : nullptr;
+    p.acc_scale = a.accum_scale;
+    p.acc_update = c.acc_update;
+    run_chunk<S, NV, COMP, NORMS, OUT>(p, c.n_vecs, lambda, a.lr, acc);
 }
 
 // One chunk, whatever its K': picks the unrolled variant (K' <= 4 or <= 8) or the streamed one, then
 // reduces the three partial sums of the workgroup and writes the chunk's partial.
-template <typename S, int LEVEL, bool NORMS, bool GOUT>
+template <typename S, int LEVEL, bool NORMS, int OUT>
 __device__ __forceinline__ void process_chunk(const StepArgs &a, const ChunkInfo &c, uint32_t chunk,
                                               float (&red)[3][kWaves]) {
     float acc[3] = {0.f, 0.f, 0.f};
+    if (c.skip) {       // uniform: this stage is not part of the call; its norms read as zero
+        if (NORMS && threadIdx.x < 3) a.partials[(size_t)threadIdx.x * a.n_chunks + chunk] = 0.f;
+        return;
+    }
     // the coefficient: one scalar for the call, or this stage's self-tuned one from device memory
     // (read through the constant address space: a scalar load; the array was last written by an
     // earlier kernel of the same stream)
@@ -413,24 +462,24 @@ __device__ __forceinline__ void process_chunk(const StepArgs &a, const ChunkInfo
     // versions to read: the K'+1 boundaries; with K' = 0 only V[tau], plus V[0] when the weight
     // gap is wanted for the norms
     if (c.kp == 0) {
-        if (NORMS && c.tau > 0) do_chunk<S, 2, false, NORMS, GOUT>(a, c, lambda, acc);
-        else do_chunk<S, 1, false, NORMS, GOUT>(a, c, lambda, acc);
+        if (NORMS && c.tau > 0) do_chunk<S, 2, false, NORMS, OUT>(a, c, lambda, acc);
+        else do_chunk<S, 1, false, NORMS, OUT>(a, c, lambda, acc);
     } else if (c.kp == 1) {
-        do_chunk<S, 2, true, NORMS, GOUT>(a, c, lambda, acc);
+        do_chunk<S, 2, true, NORMS, OUT>(a, c, lambda, acc);
     } else if (c.kp == 2) {
-        do_chunk<S, 3, true, NORMS, GOUT>(a, c, lambda, acc);
+        do_chunk<S, 3, true, NORMS, OUT>(a, c, lambda, acc);
     } else if (c.kp == 3) {
-        do_chunk<S, 4, true, NORMS, GOUT>(a, c, lambda, acc);
+        do_chunk<S, 4, true, NORMS, OUT>(a, c, lambda, acc);
     } else if (c.kp == 4) {
-        do_chunk<S, 5, true, NORMS, GOUT>(a, c, lambda, acc);
+        do_chunk<S, 5, true, NORMS, OUT>(a, c, lambda, acc);
     } else if (LEVEL >= 1 && c.kp == 5) {
-        do_chunk<S, 6, true, NORMS, GOUT>(a, c, lambda, acc);
+        do_chunk<S, 6, true, NORMS, OUT>(a, c, lambda, acc);
     } else if (LEVEL >= 1 && c.kp == 6) {
-        do_chunk<S, 7, true, NORMS, GOUT>(a, c, lambda, acc);
+        do_chunk<S, 7, true, NORMS, OUT>(a, c, lambda, acc);
     } else if (LEVEL >= 1 && c.kp == 7) {
-        do_chunk<S, 8, true, NORMS, GOUT>(a, c, lambda, acc);
+        do_chunk<S, 8, true, NORMS, OUT>(a, c, lambda, acc);
     } else if (LEVEL >= 1 && c.kp == 8) {
-        do_chunk<S, 9, true, NORMS, GOUT>(a, c, lambda, acc);
+        do_chunk<S, 9, true, NORMS, OUT>(a, c, lambda, acc);
     } else if (LEVEL >= 2) {
         constexpr uint64_t kStoreBytes = S::kStoreBytes;
         ChunkPtrs<1> p;
@@ -438,8 +487,11 @@ __device__ __forceinline__ void process_chunk(const StepArgs &a, const ChunkInfo
         p.v[0] = nullptr;
         p.out = const_cast<char *>(c.arena) + (uint64_t)((c.head + 1) % c.R) * c.slot_bytes;
         p.master = a.master ? reinterpret_cast<char *>(a.master) + c.flat_elem0 * 4 : nullptr;
-        p.g_out = GOUT ? reinterpret_cast<char *>(a.grad_out) + c.flat_elem0 * 4 : nullptr;
-        run_chunk_streamed<S, NORMS, GOUT>(p, c.arena, c.slot_bytes, c.R, c.head, c.tau, c.kp, c.n_vecs,
+        p.g_out = (OUT & 1) ? reinterpret_cast<char *>(a.grad_out) + c.flat_elem0 * 4 : nullptr;
+        p.accum = (OUT & 2) ? reinterpret_cast<char *>(a.accum) + c.flat_elem0 * 4 : nullptr;
+        p.acc_scale = a.accum_scale;
+        p.acc_update = c.acc_update;
+        run_chunk_streamed<S, NORMS, OUT>(p, c.arena, c.slot_bytes, c.R, c.head, c.tau, c.kp, c.n_vecs,
                                            lambda, a.lr, acc);
     }
     if (NORMS) {
@@ -467,7 +519,7 @@ __device__ __forceinline__ void process_chunk(const StepArgs &a, const ChunkInfo
 //                     block index is uniform, so nothing needs LDS or a barrier).
 // LEVEL 0 / 1 / 2   : largest K' of any stage is <= 4 / <= 8 / anything; paths a launch cannot
 //                     need are not compiled in, which keeps the register footprint small.
-template <typename S, bool PERSISTENT, int LEVEL, bool NORMS, bool GOUT>
+template <typename S, bool PERSISTENT, int LEVEL, bool NORMS, int OUT>
 __global__ void __launch_bounds__(kThreads) step_kernel(const StepArgs a) {
     __shared__ float red[3][kWaves];
     if constexpr (PERSISTENT) {
@@ -484,7 +536,7 @@ __global__ void __launch_bounds__(kThreads) step_kernel(const StepArgs a) {
             while (stage + 1 < a.n_stages && chunk >= tab[stage + 1].chunk_begin) ++stage;
             stage = uniform(stage);
             const ChunkInfo c = chunk_info<S>(a, tab[stage], chunk, stage);
-            process_chunk<S, LEVEL, NORMS, GOUT>(a, c, chunk, red);
+            process_chunk<S, LEVEL, NORMS, OUT>(a, c, chunk, red);
             if (NORMS) __syncthreads();     // red[] is reused by the next chunk
         }
     } else {
@@ -499,7 +551,7 @@ __global__ void __launch_bounds__(kThreads) step_kernel(const StepArgs a) {
             for (uint32_t j = 16; j < FERRET_MAX_STAGES; ++j) stage += chunk >= a.chunk_begin[j] ? 1u : 0u;
         }
         const ChunkInfo c = chunk_info<S>(a, a.stage[stage], chunk, stage);
-        process_chunk<S, LEVEL, NORMS, GOUT>(a, c, chunk, red);
+        process_chunk<S, LEVEL, NORMS, OUT>(a, c, chunk, red);
     }
 }
 
@@ -778,10 +830,22 @@ static uint32_t reserve_lds_for_cap(const ferret_plan &plan, const StepArgs &a, 
 template <typename S, bool PERSISTENT, int LEVEL>
 static hipError_t launch_step_level(const StepArgs &a, bool norms, bool gout, uint32_t grid, uint32_t dyn_lds,
                                     hipStream_t st) {
-#define FERRET_LAUNCH(NO, GO) \
-    hipLaunchKernelGGL((step_kernel<S, PERSISTENT, LEVEL, NO, GO>), dim3(grid), dim3(kThreads), dyn_lds, st, a)
-    if (norms) { if (gout) FERRET_LAUNCH(true, true); else FERRET_LAUNCH(true, false); }
-    else       { if (gout) FERRET_LAUNCH(false, true); else FERRET_LAUNCH(false, false); }
+#define FERRET_LAUNCH(NO, OUT) \
+    hipLaunchKernelGGL((step_kernel<S, PERSISTENT, LEVEL, NO, OUT>), dim3(grid), dim3(kThreads), dyn_lds, st, a)
+    if (norms) { if (gout) FERRET_LAUNCH(true, 1); else FERRET_LAUNCH(true, 0); }
+    else       { if (gout) FERRET_LAUNCH(false, 1); else FERRET_LAUNCH(false, 0); }
+#undef FERRET_LAUNCH
+    return hipGetLastError();
+}
+
+// Gradient-accumulation launches: one workgroup per chunk, every K' covered by one kernel.
+template <typename S>
+static hipError_t launch_step_accum(const StepArgs &a, bool norms, bool gout, uint32_t grid, uint32_t dyn_lds,
+                                    hipStream_t st) {
+#define FERRET_LAUNCH(NO, OUT) \
+    hipLaunchKernelGGL((step_kernel<S, false, 2, NO, OUT>), dim3(grid), dim3(kThreads), dyn_lds, st, a)
+    if (norms) { if (gout) FERRET_LAUNCH(true, 3); else FERRET_LAUNCH(true, 2); }
+    else       { if (gout) FERRET_LAUNCH(false, 3); else FERRET_LAUNCH(false, 2); }
 #undef FERRET_LAUNCH
     return hipGetLastError();
 }
@@ -808,10 +872,13 @@ int launch_step(const ferret_plan &plan, const StepArgs &a, float *norms_out, vo
     const bool norms = norms_out != nullptr, gout = a.grad_out != nullptr;
     const bool timed = g_prof.on && g_prof.used < (int32_t)g_prof.start.size();
     if (timed) (void)hipEventRecord(g_prof.start[g_prof.used], st);
-    const bool persistent = grid < a.n_chunks;
+    const bool persistent = grid < a.n_chunks && !a.accum;
     const uint32_t lds = reserve_lds_for_cap(plan, a, persistent);
     hipError_t e;
-    if (plan.prec == FERRET_F32)
+    if (a.accum)
+        e = plan.prec == FERRET_F32 ? launch_step_accum<F32Store>(a, norms, gout, a.n_chunks, lds, st)
+                                    : launch_step_accum<Bf16Store>(a, norms, gout, a.n_chunks, lds, st);
+    else if (plan.prec == FERRET_F32)
         e = persistent ? launch_step_typed<F32Store, true>(a, streamed, norms, gout, grid, lds, st)
                        : launch_step_typed<F32Store, false>(a, streamed, norms, gout, grid, lds, st);
     else

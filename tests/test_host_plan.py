@@ -251,3 +251,22 @@ def test_adaptive_step_argument_errors(lib):
     zero.set_state([0], [1])
     assert fn(zero.handle, 16, 16, None, ctypes.byref(ad), 0.01, None, None, 16, None) == B.FERRET_EINVAL
     assert "n_iters" in B.last_error()
+
+
+def test_accumulate_step_argument_errors(lib):
+    import ctypes
+    plan, _ = _plan([[64], [64]], [2, 0], R=3)
+    plan.set_state([0, 0], [1, 1])
+    fn = lib.ferret_accumulate_step
+    mode = (ctypes.c_int32 * 2)(2, 1)
+    ok = B.ferret_accumulate(16, 1.0, mode, None)
+    assert fn(plan.handle, 16, 16, None, None, 0.5, 0.01, None, None, None, None) == B.FERRET_EINVAL
+    bad = B.ferret_accumulate(None, 1.0, mode, None)
+    assert fn(plan.handle, 16, 16, None, ctypes.byref(bad), 0.5, 0.01, None, None, None, None) == B.FERRET_EINVAL
+    bad = B.ferret_accumulate(16, 1.0, (ctypes.c_int32 * 2)(3, 0), None)
+    assert fn(plan.handle, 16, 16, None, ctypes.byref(bad), 0.5, 0.01, None, None, None, None) == B.FERRET_EINVAL
+    assert "mode" in B.last_error()
+    bad = B.ferret_accumulate(16, 1.0, mode, (ctypes.c_int32 * 2)(3, 0))
+    assert fn(plan.handle, 16, 16, None, ctypes.byref(bad), 0.5, 0.01, None, None, None, None) == B.FERRET_EINVAL
+    assert "staleness" in B.last_error()
+    assert ok.scale == 1.0
