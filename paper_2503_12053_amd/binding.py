@@ -51,6 +51,11 @@ class ferret_accumulate(ctypes.Structure):
                 ("staleness", POINTER(c_int32))]
 
 
+class ferret_layer(ctypes.Structure):
+    _fields_ = [("t_f", ctypes.c_double), ("t_b", ctypes.c_double), ("n_params", ctypes.c_double),
+                ("n_acts", ctypes.c_double)]
+
+
 class FerretError(RuntimeError):
     def __init__(self, status: int, message: str):
         super().__init__(f"{STATUS_NAMES.get(status, status)}: {message}")
@@ -99,6 +104,29 @@ SIGNATURES = {
     "ferret_compensate_step": (c_int32, [_P, _P, _P, _P, c_float, c_float, _P, _P, _P, _P]),
     "ferret_compensate_step_adaptive": (c_int32, [_P, _P, _P, _P, POINTER(ferret_adaptive), c_float, _P, _P, _P, _P]),
     "ferret_accumulate_step": (c_int32, [_P, _P, _P, _P, POINTER(ferret_accumulate), c_float, c_float, _P, _P, _P, _P]),
+    "ferret_pipeline_evaluate": (c_int32, [POINTER(ferret_layer), c_int32, POINTER(c_int32), c_int32, c_int32,
+                                           POINTER(c_int32), POINTER(c_int32), POINTER(c_int32), POINTER(c_int32),
+                                           ctypes.c_double, ctypes.c_double, POINTER(ctypes.c_double),
+                                           POINTER(ctypes.c_double)]),
+    "ferret_pipeline_search": (c_int32, [POINTER(ferret_layer), c_int32, POINTER(c_int32), c_int32, ctypes.c_double,
+                                         ctypes.c_double, ctypes.c_double, ctypes.c_double, POINTER(_P)]),
+    "ferret_pipeline_plan": (c_int32, [POINTER(ferret_layer), c_int32, ctypes.c_double, ctypes.c_double,
+                                       ctypes.c_double, ctypes.c_double, POINTER(_P)]),
+    "ferret_pipeline_destroy": (None, [_P]),
+    "ferret_pipeline_feasible": (c_int32, [_P]),
+    "ferret_pipeline_n_stages": (c_int32, [_P]),
+    "ferret_pipeline_n_workers": (c_int32, [_P]),
+    "ferret_pipeline_stage_begin": (c_int32, [_P, c_int32]),
+    "ferret_pipeline_rate": (ctypes.c_double, [_P]),
+    "ferret_pipeline_memory": (ctypes.c_double, [_P]),
+    "ferret_pipeline_stage_bound": (ctypes.c_double, [_P]),
+    "ferret_pipeline_worker_delay": (c_int32, [_P, c_int32]),
+    "ferret_pipeline_worker_recompute": (c_int32, [_P, c_int32]),
+    "ferret_pipeline_worker_accum": (c_int32, [_P, c_int32, c_int32]),
+    "ferret_pipeline_worker_omit": (c_int32, [_P, c_int32, c_int32]),
+    "ferret_pipeline_stage_versions": (c_int32, [_P, c_int32, c_int32]),
+    "ferret_pipeline_n_moves": (c_int32, [_P]),
+    "ferret_pipeline_move": (c_int32, [_P, c_int32, POINTER(c_int32), POINTER(c_int32), POINTER(c_int32)]),
     "ferret_last_error": (c_char_p, []),
     "ferret_version": (c_char_p, []),
     "ferret_copy_bytes": (c_int32, [_P, _P, c_size_t, _P]),
@@ -395,3 +423,81 @@ class DeviceState:
 
     def push(self, src: torch.Tensor, stage: int = -1, with_master: bool = True, stream=None) -> None:
         ferret_push_version(self.plan, self.ring, self.master if with_master else None, stage, src, stream)
+
+
+# ---- pipeline planner (include/ferret_planner.h) -------------------------------------------------
+def _layer_array(layers):
+    arr = (ferret_layer * max(len(layers), 1))()
+    for i, (t_f, t_b, n_params, n_acts) in enumerate(layers):
+        arr[i].t_f, arr[i].t_b, arr[i].n_params, arr[i].n_acts = t_f, t_b, n_params, n_acts
+    return arr
+
+
+def ferret_pipeline_evaluate(layers, L, delay, recompute, accum, omit, c: float, v_d: float):
+    """layers: (t_f, t_b, n_params, n_acts) tuples; accum/omit: list per worker of list per stage."""
+    P, N = len(L) - 1, len(delay)
+    flat = lambda rows: (c_int32 * max(N * P, 1))(*[int(x) for r in rows for x in r])
+    R, M = ctypes.c_double(), ctypes.c_double()
+    _check(load().ferret_pipeline_evaluate(_layer_array(layers), len(layers), (c_int32 * (P + 1))(*L), P, N,
+                                           (c_int32 * max(N, 1))(*delay), (c_int32 * max(N, 1))(*recompute),
+                                           flat(accum), flat(omit), c, v_d, byref(R), byref(M)))
+    return R.value, M.value
+
+
+class Pipeline:
+    """Result of ferret_pipeline_search / ferret_pipeline_plan."""
+
+    def __init__(self, handle):
+        self.handle, self._lib = handle, load()
+
+    def __del__(self):
+        try:
+            if self.handle:
+                self._lib.ferret_pipeline_destroy(self.handle)
+                self.handle = None
+        except Exception:
+            pass
+
+    def _q(self, name, *a):
+        return getattr(self._lib, "ferret_pipeline_" + name)(self.handle, *a)
+
+    feasible = property(lambda s: bool(s._q("feasible")))
+    n_stages = property(lambda s: s._q("n_stages"))
+    n_workers = property(lambda s: s._q("n_workers"))
+    rate = property(lambda s: s._q("rate"))
+    memory = property(lambda s: s._q("memory"))
+    stage_bound = property(lambda s: s._q("stage_bound"))
+
+    @property
+    def L(self):
+        return [self._q("stage_begin", j) for j in range(self.n_stages + 1)]
+
+    def worker(self, n):
+        P = self.n_stages
+        return dict(delay=self._q("worker_delay", n), recompute=self._q("worker_recompute", n),
+                    accum=[self._q("worker_accum", n, j) for j in range(P)],
+                    omit=[self._q("worker_omit", n, j) for j in range(P)],
+                    versions=[self._q("stage_versions", n, j) for j in range(P)])
+
+    @property
+    def moves(self):
+        out = []
+        for k in range(self._q("n_moves")):
+            w, kind, st = c_int32(), c_int32(), c_int32()
+            _check(self._q("move", k, byref(w), byref(kind), byref(st)))
+            out.append((w.value, "S%d" % kind.value, st.value))
+        return out
+
+
+def ferret_pipeline_search(layers, L, t_d: float, memory_budget: float, c: float, v_d: float) -> Pipeline:
+    out = _P()
+    P = len(L) - 1
+    _check(load().ferret_pipeline_search(_layer_array(layers), len(layers), (c_int32 * (P + 1))(*L), P, t_d,
+                                         memory_budget, c, v_d, byref(out)))
+    return Pipeline(out)
+
+
+def ferret_pipeline_plan(layers, t_d: float, memory_budget: float, c: float, v_d: float) -> Pipeline:
+    out = _P()
+    _check(load().ferret_pipeline_plan(_layer_array(layers), len(layers), t_d, memory_budget, c, v_d, byref(out)))
+    return Pipeline(out)

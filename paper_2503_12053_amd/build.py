@@ -16,8 +16,10 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libferret.so")
-SOURCES = [os.path.join(CSRC, "ferret_host.cpp"), os.path.join(CSRC, "ferret_kernels.hip")]
-HEADERS = [os.path.join(CSRC, "ferret_internal.h"), os.path.join(ROOT, "include", "ferret.h")]
+SOURCES = [os.path.join(CSRC, "ferret_host.cpp"), os.path.join(CSRC, "ferret_planner.cpp"),
+           os.path.join(CSRC, "ferret_kernels.hip")]
+HEADERS = [os.path.join(CSRC, "ferret_internal.h"), os.path.join(ROOT, "include", "ferret.h"),
+           os.path.join(ROOT, "include", "ferret_planner.h")]
 ARCH = "gfx950"
 
 

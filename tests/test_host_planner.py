@@ -1,0 +1,122 @@
+"""CPU tests of libferret's pipeline planner (C++) against the planner oracle (plain Python)."""
+import random
+
+import pytest
+
+from oracle import planner_oracle as PO
+from paper_2503_12053_amd import binding as B
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _lib():
+    from paper_2503_12053_amd import build
+    build.build(verbose=False)
+    B.load()
+
+
+def _layers(rng, n):
+    return [(rng.uniform(0.5, 2.0), rng.uniform(0.5, 3.0), float(rng.randint(10, 500)), float(rng.randint(5, 200)))
+            for _ in range(n)]
+
+
+def _po(layers):
+    return [PO.Layer(*x) for x in layers]
+
+
+def _random_partition(rng, n):
+    cuts = sorted(rng.sample(range(1, n), rng.randint(0, n - 1)))
+    return [0] + cuts + [n]
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_cost_model_matches_oracle(seed):
+    rng = random.Random(seed)
+    layers = _layers(rng, 8)
+    L = _random_partition(rng, 8)
+    P, N = len(L) - 1, rng.randint(1, 4)
+    C = PO.Config(list(range(N)), [rng.randint(0, 1) for _ in range(N)], [[1] * P for _ in range(N)],
+                  [[0] * P for _ in range(N)])
+    for _ in range(rng.randint(0, 8)):
+        mv = list(PO.moves(P, C))
+        if not mv:
+            break
+        C = PO.apply_move(P, C, rng.choice(mv))
+    want = PO.evaluate(PO.stages_of(_po(layers), L), C, 0.04, 1.5)
+    got = B.ferret_pipeline_evaluate(layers, L, C.delay, C.recompute, C.accum, C.omit, 0.04, 1.5)
+    assert got[0] == pytest.approx(want[0], rel=1e-13, abs=1e-300) and got[1] == pytest.approx(want[1], rel=1e-13)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_search_takes_the_same_moves_as_the_oracle(seed):
+    rng = random.Random(50 + seed)
+    layers = _layers(rng, 7)
+    L = _random_partition(rng, 7)
+    S = PO.stages_of(_po(layers), L)
+    t_d = (S.t_f + S.t_b) / rng.uniform(0.8, 3.5)
+    c, v = 0.03, 1.0
+    N0 = -(-(S.t_f + S.t_b) // t_d)
+    full_mem = PO.evaluate(S, PO.Config(list(range(int(N0))), [0] * int(N0), [[1] * len(S.w)] * int(N0),
+                                        [[0] * len(S.w)] * int(N0)), c, v)[1]
+    for frac in (1.5, 0.8, 0.5, 0.25, 0.05):
+        M = full_mem * frac
+        want_C, want_R, want_M, want_trace = PO.search(S, t_d, M, c, v)
+        got = B.ferret_pipeline_search(layers, L, t_d, M, c, v)
+        assert got.feasible == (want_C is not None)
+        assert got.rate == pytest.approx(want_R, rel=1e-12, abs=1e-300)
+        if want_C is None:
+            continue
+        assert got.memory == pytest.approx(want_M, rel=1e-12) and got.memory <= M
+        assert got.moves == [(n, k, j) for n, k, j in want_trace]
+        assert got.n_workers == len(want_C.delay)
+        for n in range(got.n_workers):
+            wk = got.worker(n)
+            assert (wk["delay"], wk["recompute"], wk["accum"], wk["omit"]) == \
+                (want_C.delay[n], want_C.recompute[n], want_C.accum[n], want_C.omit[n])
+            P = len(S.w)
+            assert wk["versions"] == [1 + -(-(P - j - 1) // wk["accum"][j]) - wk["omit"][j] for j in range(P)]
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_plan_matches_oracle(seed):
+    rng = random.Random(90 + seed)
+    layers = _layers(rng, 6)
+    t_d = rng.uniform(1.0, 3.0)
+    M = sum(x[2] + x[3] for x in layers) * rng.uniform(0.8, 4.0)
+    want = PO.plan(_po(layers), t_d, M, 0.05, 1.0)
+    got = B.ferret_pipeline_plan(layers, t_d, M, 0.05, 1.0)
+    assert got.rate == pytest.approx(want["R"], rel=1e-12, abs=1e-300)
+    if want["L"] is None:
+        assert not got.feasible
+        return
+    assert got.feasible and got.L == want["L"] and got.stage_bound == pytest.approx(want["t_c"], rel=1e-14)
+    assert got.memory <= M
+
+
+def test_plan_feeds_the_update_path():
+    """The planner's per-stage version counts are what ferret_plan_buckets takes as ring depths."""
+    layers = [(1.0, 2.0, 4096.0, 100.0)] * 6
+    got = B.ferret_pipeline_plan(layers, 1.0, 1e9, 0.01, 1.0)          # generous budget: nothing pruned
+    P = got.n_stages
+    assert got.feasible and got.moves == [] and got.worker(0)["versions"] == [P - j for j in range(P)]
+    tau = [v - 1 for v in got.worker(0)["versions"]]
+    L = got.L
+    tensors = [(4096, j) for j in range(P) for _ in range(L[j + 1] - L[j])]
+    plan = B.ferret_plan_buckets(tensors, P, tau, B.FERRET_ITERS_FULL, B.FERRET_RING_DEPTH_MINIMAL)
+    assert [plan.stage_ring_depth(j) for j in range(P)] == got.worker(0)["versions"]
+
+
+def test_planner_argument_errors():
+    with pytest.raises(B.FerretError):
+        B.ferret_pipeline_plan([], 1.0, 1.0, 0.1, 1.0)
+    with pytest.raises(B.FerretError):
+        B.ferret_pipeline_plan([(0.0, 1.0, 1.0, 1.0)], 1.0, 1.0, 0.1, 1.0)
+    with pytest.raises(B.FerretError):
+        B.ferret_pipeline_plan([(1.0, 1.0, 1.0, 1.0)], 0.0, 1.0, 0.1, 1.0)
+    with pytest.raises(B.FerretError):
+        B.ferret_pipeline_search([(1.0, 1.0, 1.0, 1.0)] * 3, [0, 2, 2, 3], 1.0, 1.0, 0.1, 1.0)
+    with pytest.raises(B.FerretError):
+        B.ferret_pipeline_evaluate([(1.0, 1.0, 1.0, 1.0)], [0, 1], [0], [0], [[0]], [[0]], 0.1, 1.0)   # c^a = 0
+    # a budget below one copy of the model: the search ends by removing every worker (S4), rate 0
+    tiny = B.ferret_pipeline_search([(1.0, 1.0, 10.0, 1.0)] * 2, [0, 1, 2], 1.0, 1.0, 0.1, 1.0)
+    assert tiny.rate == 0.0 and tiny.memory == 0.0
+    assert all(tiny.worker(n)["delay"] < 0 for n in range(tiny.n_workers))
