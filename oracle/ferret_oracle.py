@@ -39,8 +39,12 @@ def build(force: bool = False) -> str:
 def _load():
     global _lib
     if _lib is None:
-        build()
-        lib = ctypes.CDLL(_LIB)
+        override = os.environ.get("FERRET_ORACLE_LIB")      # tests of the pins load a deliberately broken build
+        if override:
+            lib = ctypes.CDLL(override)
+        else:
+            build()
+            lib = ctypes.CDLL(_LIB)
         pp = ctypes.POINTER(ctypes.c_void_p)
         lib.ferret_oracle_effective_iters.restype = ctypes.c_int32
         lib.ferret_oracle_effective_iters.argtypes = [ctypes.c_int32, ctypes.c_int32]

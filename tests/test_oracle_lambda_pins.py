@@ -72,15 +72,18 @@ def test_exact_line_minimum_with_the_right_step_size():
 
 
 def test_moving_averages_converge_geometrically():
-    """Constant inputs: after n calls v_r = (1 - alpha^n) g and v_a = (1 - alpha^n) g^2 (V1 - V0)."""
+    """Constant inputs: after n calls v_r = (1 - alpha^n) g and v_a = (1 - alpha^n) g^2 (V1 - V0)
+    (alpha = 3/4: every intermediate value is an exact binary fraction, and the two weights of the
+    average differ, so swapping them shows)."""
     g, V0, V1 = _f32([2.0, -1.0]), _f32([1.0, 1.0]), _f32([1.25, 0.5])
-    alpha = 0.5
+    alpha = 0.75
     r, a = _f32([0, 0]), _f32([0, 0])
     for n in range(1, 9):
         _, r, a, _ = O.lambda_update(g, V0, V1, 0.2, alpha, 0.0, r, a)
         f = 1 - alpha ** n
         assert np.array_equal(r, _f32([2 * f, -1 * f]))
         assert np.array_equal(a, _f32([4 * 0.25 * f, 1 * -0.5 * f]))
+    assert r[0] == np.float32(2 * (1 - 6561 / 65536))
 
 
 def test_zero_learning_rate_keeps_lambda_and_matches_fixed_lambda_path():
