@@ -83,6 +83,49 @@ def cpu_baseline(w, host, plan, budget_s=20.0):
             "single_thread_value": n1 / t1}
 
 
+def per_tensor_contrast(w, args, torch, B, W):
+    """The same step issued as one launch per parameter tensor (what a per-tensor optimizer loop does)."""
+    states = []
+    for j in range(w.n_stages):
+        d = W.generate_stage(w, j)
+        pos = 0
+        for _, n in w.stage_tensors(j):
+            plan = B.ferret_plan_buckets([(n, 0)], 1, [w.staleness[j]], w.n_iters, w.ring_depth,
+                                         B.FERRET_F32 if w.precision == "f32" else B.FERRET_BF16_MASTER_F32)
+            st = B.DeviceState(plan, [(n, 0)], want_grad_out=False, want_norms=not args.no_norms)
+            head = st.load_versions(0, [v[pos:pos + n] for v in d.versions])
+            st.set_flat(st.grads, 0, d.grads[pos:pos + n])
+            if d.master is not None:
+                st.set_flat(st.master, 0, d.master[pos:pos + n])
+            plan.set_state([head], [w.ring_depth])
+            states.append(st)
+            pos += n
+    norms = not args.no_norms
+
+    def one_step():
+        for st in states:
+            st.step(w.lam, w.lr, norms=norms, grad_out=False)
+            st.commit()
+
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_step()
+    torch.cuda.synchronize()
+    elapsed = (time.perf_counter() - t0) / args.steps
+    step_bytes = sum(st.plan.step_bytes for st in states)
+    log(f"per-tensor launches: {len(states)} launches per step, {elapsed * 1e6:.1f} us wall per step, "
+        f"{w.numel / elapsed:.3e} params/s, {step_bytes / elapsed / 1e9:.0f} GB/s algorithmic")
+    print(json.dumps({"metric": "compensated_params_per_sec", "value": w.numel / elapsed, "unit": "params/s",
+                      "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": elapsed * 1e3,
+                      "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.precision,
+                      "data": "synthetic",
+                      "config": {"workload": w.name, "mode": "one launch per tensor", "launches_per_step": len(states)}}),
+          flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -100,6 +143,11 @@ def main():
                     help="time the self-tuned-lambda step (all of Alg. 1) instead of the fixed-lambda step")
     ap.add_argument("--accumulate", type=int, default=0, metavar="CA",
                     help="time gradient accumulation (T2): one step = CA arrivals per stage, the last one updates")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one full ring rotation (ring_depth steps) in a HIP graph and time replays; "
+                         "removes the launch overhead that dominates the small workloads")
+    ap.add_argument("--per-tensor", action="store_true",
+                    help="contrast: one plan and one launch per tensor instead of one bucketed launch per step")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="do not record per-launch HIP events (roofline is then taken from wall time)")
     args = ap.parse_args()
@@ -121,6 +169,8 @@ def main():
     w = W.make_workload(args.config)
     if args.iters is not None:
         w.n_iters = args.iters
+    if args.per_tensor:
+        return per_tensor_contrast(w, args, torch, B, W)
     tuning = None
     if args.blocks_per_cu or args.slot_align or args.slot_skew:
         tuning = dict(blocks_per_cu=args.blocks_per_cu, slot_align_elems=args.slot_align,
@@ -183,14 +233,39 @@ def main():
         one_step()
     torch.cuda.synchronize()
 
-    if not args.no_kernel_events:
+    if args.graph:
+        # after ring_depth steps every head is back where it started, so a graph of one rotation
+        # can be replayed for ever; the host-side commits inside the capture only move integers
+        R = w.ring_depth
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                for _ in range(R):
+                    one_step()
+        torch.cuda.current_stream().wait_stream(side)
+        replays = max(args.steps // R, 1)
+        args.steps = replays * R
+        args.no_kernel_events = True
+        for _ in range(3):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(replays):
+            graph.replay()
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+        log(f"graph of {R} steps replayed {replays} times")
+    elif not args.no_kernel_events:
         B.ferret_profile_begin(args.steps * max(args.accumulate, 1))
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        one_step()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
+    if not args.graph:
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            one_step()
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
     n_launch = args.steps * max(args.accumulate, 1)
     kernel_ms = B.ferret_profile_end(n_launch) if not args.no_kernel_events else [elapsed * 1e3 / args.steps]
 
@@ -234,7 +309,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "params": w.numel, "stages": w.n_stages, "staleness": w.staleness,
                    "ring_depth": w.ring_depth, "n_iters": w.n_iters, "lambda": w.lam, "lr": w.lr,
-                   "norms": norms, "adaptive_lambda": bool(args.adaptive), "accumulation_steps": args.accumulate,
+                   "norms": norms, "adaptive_lambda": bool(args.adaptive), "accumulation_steps": args.accumulate, "hip_graph": bool(args.graph),
                    "chunk_elems": plan.chunk_elems,
                    "algorithmic_bytes_per_step": step_bytes},
         "hbm_gbs_wall": step_bytes / (elapsed / args.steps) / 1e9,

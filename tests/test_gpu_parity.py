@@ -290,3 +290,40 @@ def test_copy_bytes():
     B.ferret_copy_bytes(b, a, a.numel() * 4)
     torch.cuda.synchronize()
     assert torch.equal(a, b)
+
+
+# ---- HIP graph capture -----------------------------------------------------------------------------
+def test_graph_of_one_ring_rotation_replays_like_eager_steps():
+    """The library launches on the caller's stream and allocates nothing, so a full rotation of the ring
+    (ring_depth steps; afterwards every head is back at its starting slot) can be captured once and
+    replayed.  Every replay is checked against eager execution of the same steps, with eager work and
+    synchronisations between the replays."""
+    w = W.custom_workload("graph", [[60_000, 8], [20_000]], [2, 1], 3, -1, seed=61)
+    plan_g, st_g, _ = PU.load_workload(w, amplified=True)
+    plan_e, st_e, _ = PU.load_workload(w, amplified=True)
+    R = w.ring_depth
+
+    def rotation(st):
+        for _ in range(R):
+            st.step(w.lam, w.lr)
+            st.commit()
+
+    heads0 = plan_g.get_state()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            rotation(st_g)
+    torch.cuda.current_stream().wait_stream(side)
+    assert plan_g.get_state() == heads0                     # host state is back at the start
+    for replay in range(4):
+        g = W.draw_grads(w, 0, w.stage_numel()[0], amplified=True, step=100 + replay)
+        for st in (st_g, st_e):                             # new gradients, eager work between replays
+            st.set_flat(st.grads, 0, g)
+        torch.cuda.synchronize()
+        graph.replay()
+        rotation(st_e)
+        torch.cuda.synchronize()
+        assert torch.equal(st_g.ring, st_e.ring), f"replay {replay}"
+        assert torch.equal(st_g.norms, st_e.norms) and torch.equal(st_g.grad_out, st_e.grad_out)
