@@ -103,18 +103,65 @@ struct SearchResult {
     double rate = 0, memory = 0;
 };
 
+// Alg. 2 for one value of c^r.  Everything a candidate move needs is cached so that a round of the
+// while-loop costs O(N P (P + N)) additions and no exponentials:
+//   numer[i][k]   exp(-c((P+k) t^f + (P-i+k) t^b + c^r (P-i+k) t^f)) V_D, shared by all workers
+//   term[n][i]    stage i's share of worker n's rate, |w_i|/W * 1/c^a * sum_k numer[i][k]/(lcm_i * period)
+// and every sum is formed in the same order as a plain evaluation of the cost model would form it
+// (stage terms left to right, A_{i,k} for k = 0, 1, ..., workers in index order), so the decisions
+// do not depend on the caching.
 SearchResult itersearch(const StageAgg &S, double t_d, int c_r, double M, double c, double v_d) {
     const int P = S.P();
     SearchResult out;
     const int N = (int)std::ceil((S.t_f + S.t_b + c_r * S.t_f) / t_d);
+    const double r = c_r, period = S.t_f + S.t_b + r * S.t_f;
+
+    std::vector<std::vector<double>> numer(P);
+    auto numerator = [&](int i, int k) -> double {
+        std::vector<double> &row = numer[i];
+        while ((int)row.size() <= k) {
+            const int j = (int)row.size();
+            const double expo = -c * ((P + j) * S.t_f + (P - i + j) * S.t_b + r * (P - i + j) * S.t_f);
+            row.push_back(std::exp(expo) * v_d);
+        }
+        return row[k];
+    };
+    // stage i's term for accumulation steps ca and LCM denominator lcm
+    auto stage_term = [&](int i, int ca, long long lcm) {
+        double sum = 0;
+        for (int k = 0; k < ca; ++k) sum += numerator(i, k) / ((double)lcm * period);
+        return S.w[i] / S.total_w * (1.0 / ca) * sum;
+    };
+    auto suffix_lcm = [&](const Worker &wk, std::vector<long long> &suf) {
+        suf.assign(P + 1, 1);
+        for (int k = P - 1; k >= 0; --k) suf[k] = lcm_ll(suf[k + 1], wk.omit[k] + 1);
+    };
+    auto stage_mem = [&](const Worker &wk, int i) {
+        const int versions = 1 + ceil_div(P - i - 1, wk.accum[i]) - wk.omit[i];
+        return versions * (S.w[i] + S.a[i] - wk.recompute * S.inner[i]);
+    };
+
     out.workers.resize(N);
+    std::vector<std::vector<double>> term(N, std::vector<double>(P)), memt(N, std::vector<double>(P));
     std::vector<double> rate(N), mem(N);
+    std::vector<long long> suf;
+    auto refresh = [&](int n) {          // recompute worker n's cached terms and sums from its configuration
+        const Worker &wk = out.workers[n];
+        suffix_lcm(wk, suf);
+        double rr = 0, mm = 0;
+        for (int i = 0; i < P; ++i) {
+            term[n][i] = stage_term(i, wk.accum[i], suf[i]);
+            memt[n][i] = stage_mem(wk, i);
+            rr += term[n][i];
+            mm += memt[n][i];
+        }
+        rate[n] = rr; mem[n] = mm;
+    };
     for (int n = 0; n < N; ++n) {
         Worker &wk = out.workers[n];
         wk.delay = n; wk.recompute = c_r;
         wk.accum.assign(P, 1); wk.omit.assign(P, 0);
-        rate[n] = worker_rate(S, wk, c, v_d);
-        mem[n] = worker_memory(S, wk);
+        refresh(n);
     }
     auto total = [&](const std::vector<double> &x) {
         double t = 0;
@@ -122,16 +169,13 @@ SearchResult itersearch(const StageAgg &S, double t_d, int c_r, double M, double
         return t;
     };
     double R = total(rate), Mem = total(mem);
+    std::vector<double> cand_term(P), cand_mem(P);
     while (Mem > M) {
         bool found = false;
         double best_merit = -1;
         Move best{};
-        Worker best_worker;
-        double best_rate = 0, best_mem = 0;
-        auto consider = [&](int n, int kind, int j, const Worker &cand, bool removed) {
-            const double r2 = removed ? 0.0 : worker_rate(S, cand, c, v_d);
-            const double m2 = removed ? 0.0 : worker_memory(S, cand);
-            // totals after the move, formed exactly as a full re-evaluation would form them
+        // totals with worker n replaced by (r2, m2), or dropped
+        auto consider = [&](int n, int kind, int j, double r2, double m2, bool removed) {
             double R2 = 0, M2 = 0;
             for (int k = 0; k < N; ++k) {
                 if (out.workers[k].delay < 0) continue;
@@ -141,35 +185,43 @@ SearchResult itersearch(const StageAgg &S, double t_d, int c_r, double M, double
             const double dR = R2 - R, dM = M2 - Mem;
             if (dM >= 0) return;
             const double merit = dR >= 0 ? std::numeric_limits<double>::infinity() : dM / dR;
-            if (merit > best_merit) {
-                found = true; best_merit = merit; best = Move{n, kind, j};
-                best_worker = cand; best_rate = r2; best_mem = m2;
-                if (removed) best_worker.delay = -1;
-            }
+            if (merit > best_merit) { found = true; best_merit = merit; best = Move{n, kind, j}; }
         };
         for (int n = 0; n < N; ++n) {
             const Worker &wk = out.workers[n];
             if (wk.delay < 0) continue;
-            for (int j = 0; j + 1 < P; ++j) {
+            suffix_lcm(wk, suf);
+            for (int j = 0; j + 1 < P; ++j) {           // S2: only stage j's term and memory change
                 const int nxt = next_accum(P, j, wk.accum[j]);
-                if (wk.omit[j] == 0 && nxt > 0) {
-                    Worker cand = wk; cand.accum[j] = nxt;
-                    consider(n, 2, j, cand, false);
-                }
+                if (wk.omit[j] != 0 || nxt == 0) continue;
+                const double tj = stage_term(j, nxt, suf[j]);
+                const double mj = (1 + ceil_div(P - j - 1, nxt)) * (S.w[j] + S.a[j] - wk.recompute * S.inner[j]);
+                double r2 = 0, m2 = 0;
+                for (int i = 0; i < P; ++i) { r2 += i == j ? tj : term[n][i]; m2 += i == j ? mj : memt[n][i]; }
+                consider(n, 2, j, r2, m2, false);
             }
-            for (int j = 0; j + 1 < P; ++j)
-                if (wk.omit[j] == 0 && ceil_div(P - j - 1, wk.accum[j]) == 1) {
-                    Worker cand = wk; cand.accum[j] = 1; cand.omit[j] = P - 1 - j;
-                    consider(n, 3, j, cand, false);
+            for (int j = 0; j + 1 < P; ++j) {           // S3: the LCM of every stage i <= j changes
+                if (wk.omit[j] != 0 || ceil_div(P - j - 1, wk.accum[j]) != 1) continue;
+                long long lcm = lcm_ll(suf[j + 1], (long long)(P - 1 - j) + 1);
+                double r2 = 0, m2 = 0;
+                for (int i = j; i >= 0; --i) {
+                    if (i < j) lcm = lcm_ll(lcm, wk.omit[i] + 1);
+                    cand_term[i] = stage_term(i, i == j ? 1 : wk.accum[i], lcm);
                 }
+                const double mj = (1 + ceil_div(P - j - 1, 1) - (P - 1 - j)) * (S.w[j] + S.a[j] - wk.recompute * S.inner[j]);
+                for (int i = 0; i < P; ++i) { r2 += i <= j ? cand_term[i] : term[n][i]; m2 += i == j ? mj : memt[n][i]; }
+                consider(n, 3, j, r2, m2, false);
+            }
             bool all_omitted = true;
             for (int j = 0; j + 1 < P; ++j) all_omitted &= wk.omit[j] != 0;
-            if (all_omitted) consider(n, 4, -1, wk, true);
+            if (all_omitted) consider(n, 4, -1, 0.0, 0.0, true);
         }
         if (!found) { out.feasible = false; out.rate = 0; out.memory = Mem; return out; }
-        out.workers[best.worker] = best_worker;
-        rate[best.worker] = best_rate;
-        mem[best.worker] = best_mem;
+        Worker &wk = out.workers[best.worker];
+        if (best.kind == 2) wk.accum[best.stage] = next_accum(P, best.stage, wk.accum[best.stage]);
+        else if (best.kind == 3) { wk.accum[best.stage] = 1; wk.omit[best.stage] = P - 1 - best.stage; }
+        else wk.delay = -1;
+        if (wk.delay >= 0) refresh(best.worker);
         out.trace.push_back(best);
         R = total(rate);
         Mem = total(mem);
@@ -283,6 +335,7 @@ ferret_status ferret_pipeline_plan(const ferret_layer *layers, int32_t n_layers,
 
     ferret_pipeline *best = new (std::nothrow) ferret_pipeline();
     if (!best) { set_error("%s: out of host memory", who); return FERRET_ENOMEM; }
+    std::vector<int32_t> previous_L;      // consecutive bounds often give the same partition: search it once
     for (double t_c : bounds) {
         std::vector<int32_t> L{0};
         double t_sum = 0;
@@ -291,6 +344,8 @@ ferret_status ferret_pipeline_plan(const ferret_layer *layers, int32_t n_layers,
             if (t_sum > t_c) { L.push_back(i); t_sum = per[i]; }
         }
         L.push_back(n_layers);
+        if (L == previous_L) continue;      // same partition as the smaller bound before it: same result, and
+        previous_L = L;                     // the comparison below is strict, so the first bound stays recorded
         StageAgg S;
         aggregate(layers, n_layers, L.data(), (int)L.size() - 1, S);
         if ((S.t_f + S.t_b + S.t_f) / t_d > 4096) continue;
