@@ -327,3 +327,36 @@ def test_graph_of_one_ring_rotation_replays_like_eager_steps():
         torch.cuda.synchronize()
         assert torch.equal(st_g.ring, st_e.ring), f"replay {replay}"
         assert torch.equal(st_g.norms, st_e.norms) and torch.equal(st_g.grad_out, st_e.grad_out)
+
+
+# ---- limits of the interface -----------------------------------------------------------------------
+@pytest.mark.parametrize("n_stages", [17, 40, B.FERRET_MAX_STAGES])
+def test_many_stages_up_to_the_maximum(n_stages):
+    """More than 16 stages takes the second half of the scalar stage lookup; 64 is the documented maximum."""
+    rng = np.random.default_rng(n_stages)
+    sizes = [[int(rng.integers(1, 6000))] + ([int(rng.integers(1, 300))] if j % 3 == 0 else []) for j in range(n_stages)]
+    tau = [int(rng.integers(0, 8)) for _ in range(n_stages)]
+    w = W.custom_workload(f"stages{n_stages}", sizes, tau, 8, 3, seed=70 + n_stages)
+    _run(w, True)
+    w16 = W.custom_workload(f"stages{n_stages}_bf16", sizes, tau, 8, -1, precision="bf16", seed=71 + n_stages)
+    _run(w16, True)
+
+
+@pytest.mark.parametrize("precision", ["f32", "bf16"])
+def test_deep_ring_and_long_iteration_chains(precision):
+    """tau = 32 with one iteration per version step: the streamed path's batches of four plus a remainder;
+    tau = 9 and 8 sit on both sides of the unrolled limit."""
+    w = W.custom_workload("deep_ring", [[9_000], [5_000], [5_000], [3_000]], [32, 9, 8, 30], 33, -1, precision=precision,
+                          seed=72, lam=0.05)
+    w.drift_std = 0.01
+    _run(w, False)
+    w2 = W.custom_workload("deep_ring_k7", [[9_000], [5_000]], [32, 20], 33, 7, precision=precision, seed=73, lam=0.3)
+    _run(w2, True, n_iters=7)
+
+
+@pytest.mark.parametrize("chunk", [65_536, 1 << 20])
+def test_large_chunks_loop_inside_a_workgroup(chunk):
+    w = W.custom_workload("big_chunks", [[1_500_000, 77], [300_001]], [3, 1], 4, 2, seed=74)
+    _run(w, True, chunk_elems=chunk)
+    w16 = W.custom_workload("big_chunks_bf16", [[1_500_000, 77], [300_001]], [3, 1], 4, 2, precision="bf16", seed=75)
+    _run(w16, True, chunk_elems=chunk)
