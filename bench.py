@@ -75,10 +75,11 @@ def cpu_baseline(w, host, plan, budget_s=20.0):
             break
         stages.append(j)
         acc += w.stage_numel()[j]
-    t1, n1 = one_step(1, stages)
-    tn, nn = one_step(cores, stages)
+    reps = max(1, min(5, int(budget_s * 0.4 / max(acc / rate1, 1e-3))))
+    t1, n1 = min(one_step(1, stages) for _ in range(reps))
+    tn, nn = min(one_step(cores, stages) for _ in range(reps))
     sample = (f"one step of stages {stages[0]}..{stages[-1]} of {w.name} ({n1} of {w.numel} parameters), "
-              f"fp64 oracle, 1 thread {t1:.2f} s, {cores} threads {tn:.2f} s")
+              f"fp64 oracle, best of {reps}: 1 thread {t1:.2f} s, {cores} threads {tn:.2f} s")
     return {"value": nn / tn, "unit": "params/s", "cores": cores, "kind": "oracle", "sample": sample,
             "single_thread_value": n1 / t1}
 
@@ -292,7 +293,18 @@ def main():
     ev[1].record()
     torch.cuda.synchronize()
     copy_gbs = 2 * n_copy * 10 / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e9
-    log(f"copy kernel ceiling: {copy_gbs:.0f} GB/s (read+write, {n_copy / 1e6:.0f} MB)")
+    sink = torch.zeros(4, dtype=torch.int32, device=dev)
+    n_read = plan.ring_bytes // 16 * 16
+    for _ in range(3):
+        B.ferret_read_bytes(st.ring, n_read, sink)
+    ev[0].record()
+    for _ in range(10):
+        B.ferret_read_bytes(st.ring, n_read, sink)
+    ev[1].record()
+    torch.cuda.synchronize()
+    read_gbs = n_read * 10 / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e9
+    log(f"context: copy kernel {copy_gbs:.0f} GB/s (read+write, {n_copy / 1e6:.0f} MB), "
+        f"read-only kernel {read_gbs:.0f} GB/s ({n_read / 1e6:.0f} MB)")
 
     result = {
         "metric": "compensated_params_per_sec",
@@ -316,7 +328,7 @@ def main():
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic(w.name),
                      "kernel": "ferret::step_kernel", "kernel_avg_us": k_avg * 1e3, "kernel_median_us": k_med * 1e3,
-                     "copy_kernel_gbs": copy_gbs},
+                     "copy_kernel_gbs": copy_gbs, "read_kernel_gbs": read_gbs},
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, host, plan)

@@ -272,6 +272,10 @@ const char *ferret_version(void);
  * 16-byte aligned pointers).  Measures the streaming ceiling of the machine with the same
  * launch shape as the step; not part of the method. */
 ferret_status ferret_copy_bytes(void *dst, const void *src, size_t n_bytes, void *hip_stream);
+/* Read-only companion: streams n_bytes from src and discards them (sink: device, >= 16 bytes, written
+ * only in the practically impossible case that the data sums to a magic value; it exists so that the
+ * loads cannot be optimised away).  The read ceiling of the machine for the same launch shape. */
+ferret_status ferret_read_bytes(const void *src, size_t n_bytes, void *sink, void *hip_stream);
 
 /* ---- measurement ------------------------------------------------------------------------------ */
 /* Per-launch timing of the fused step kernel with HIP events recorded on the step's own stream,

@@ -130,6 +130,7 @@ SIGNATURES = {
     "ferret_last_error": (c_char_p, []),
     "ferret_version": (c_char_p, []),
     "ferret_copy_bytes": (c_int32, [_P, _P, c_size_t, _P]),
+    "ferret_read_bytes": (c_int32, [_P, c_size_t, _P, _P]),
     "ferret_profile_begin": (c_int32, [c_int32]),
     "ferret_profile_end": (c_int32, [POINTER(c_float), c_int32, POINTER(c_int32)]),
 }
@@ -236,6 +237,10 @@ def ferret_accumulate_step(plan: "Plan", ring, grads, master, accum, scale: floa
 
 def ferret_copy_bytes(dst, src, n_bytes: int, stream=None) -> None:
     _check(load().ferret_copy_bytes(_ptr(dst), _ptr(src), n_bytes, _stream(stream)))
+
+
+def ferret_read_bytes(src, n_bytes: int, sink, stream=None) -> None:
+    _check(load().ferret_read_bytes(_ptr(src), n_bytes, _ptr(sink), _stream(stream)))
 
 
 def ferret_profile_begin(capacity: int) -> None:

@@ -493,6 +493,17 @@ ferret_status ferret_copy_bytes(void *dst, const void *src, size_t n_bytes, void
     return FERRET_OK;
 }
 
+ferret_status ferret_read_bytes(const void *src, size_t n_bytes, void *sink, void *hip_stream) {
+    if (!src || !sink || !aligned16(src) || !aligned16(sink) || (n_bytes & 15u)) {
+        set_error("read_bytes: need non-null 16-byte aligned pointers and a multiple of 16 bytes");
+        return FERRET_EINVAL;
+    }
+    if (n_bytes == 0) return FERRET_OK;
+    int err = launch_read(src, n_bytes, sink, hip_stream);
+    if (err) { set_error("read_bytes: launch failed: %s", device_error_string(err)); return FERRET_EDEVICE; }
+    return FERRET_OK;
+}
+
 ferret_status ferret_profile_begin(int32_t capacity) {
     if (capacity < 1 || capacity > (1 << 20)) { set_error("profile_begin: capacity = %d", capacity); return FERRET_EINVAL; }
     int err = profile_begin(capacity);

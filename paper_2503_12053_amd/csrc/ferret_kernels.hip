@@ -735,6 +735,21 @@ __global__ void __launch_bounds__(kThreads) copy_kernel(v4u *dst, const v4u *src
         if (base + (size_t)u * kThreads < n_vecs) st(&dst[base + (size_t)u * kThreads], x[u]);
 }
 
+// Plain streaming read with the same shape; the data is summed and compared with a value it never has.
+__global__ void __launch_bounds__(kThreads) read_kernel(const v4u *src, size_t n_vecs, v4u *sink) {
+    const size_t base = (size_t)blockIdx.x * kThreads * kCopyVecsPerLane + threadIdx.x;
+    v4u x[kCopyVecsPerLane];
+#pragma unroll
+    for (int u = 0; u < kCopyVecsPerLane; ++u) {
+        x[u] = v4u{0u, 0u, 0u, 0u};
+        if (base + (size_t)u * kThreads < n_vecs) x[u] = ld(&src[base + (size_t)u * kThreads]);
+    }
+    v4u s = x[0];
+#pragma unroll
+    for (int u = 1; u < kCopyVecsPerLane; ++u) s += x[u];
+    if (s.x == 0x9e3779b9u && s.y == 0x7f4a7c15u && s.z == 0xf39cc060u && s.w == 0x5cedc834u) sink[0] = s;
+}
+
 // ---- per-launch event timing of the step kernel ---------------------------------------------------
 struct Profiler {
     std::vector<hipEvent_t> start, stop;
@@ -926,6 +941,16 @@ int launch_copy(void *dst, const void *src, size_t n_bytes, void *stream) {
     if (blocks > 0x7fffffffull) return (int)hipErrorInvalidValue;
     hipLaunchKernelGGL(copy_kernel, dim3((uint32_t)blocks), dim3(kThreads), 0, static_cast<hipStream_t>(stream),
                        static_cast<v4u *>(dst), static_cast<const v4u *>(src), n_vecs);
+    return (int)hipGetLastError();
+}
+
+int launch_read(const void *src, size_t n_bytes, void *sink, void *stream) {
+    const size_t n_vecs = n_bytes / 16;
+    const size_t per_block = (size_t)kThreads * kCopyVecsPerLane;
+    const size_t blocks = (n_vecs + per_block - 1) / per_block;
+    if (blocks > 0x7fffffffull) return (int)hipErrorInvalidValue;
+    hipLaunchKernelGGL(read_kernel, dim3((uint32_t)blocks), dim3(kThreads), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const v4u *>(src), n_vecs, static_cast<v4u *>(sink));
     return (int)hipGetLastError();
 }
 
