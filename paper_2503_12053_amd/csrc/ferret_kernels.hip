@@ -9,18 +9,21 @@
 //                 new <- V[tau] - eta * g        (bf16 storage: on the fp32 master, then
 //                                                 round-to-nearest-even to bf16)
 //
-// Design for the machine:
-//   * every operand is touched exactly once, with 128-bit loads/stores; consecutive lanes of a
-//     64-wide wavefront touch consecutive 16-byte vectors, so a wavefront moves 1 KiB per
-//     instruction per stream;
-//   * all loads of a group (gradient + K'+1 versions, kUnroll vectors each) are issued before
-//     the first arithmetic, so each lane keeps (K'+2)*kUnroll 16-byte requests in flight;
-//   * a stage's tensors are one flat bucket; the stage table (48 B per stage) arrives as a
-//     kernel argument, is copied to LDS once per workgroup, and a persistent grid strides over
-//     fixed-size chunks, looking up the chunk's stage in LDS;
+// Design for the machine (every choice below was measured on MI355X):
+//   * every operand is touched exactly once, with 128-bit (fp32) / 64-bit (bf16) non-temporal
+//     accesses; consecutive lanes of a 64-wide wavefront touch consecutive vectors, so every
+//     access of a wavefront is one contiguous run of memory;
+//   * one workgroup of 256 lanes per chunk of 1024 fp32 / 2048 bf16 elements: all loads of a chunk
+//     (gradient + K'+1 versions) are issued before the first arithmetic, and the hardware
+//     dispatcher balances the load; a cap on resident workgroups per CU (unused LDS) keeps the
+//     bytes in flight at the measured optimum for large steps;
+//   * a stage's tensors are one flat bucket; the stage table (48 B per stage) arrives as a kernel
+//     argument; the chunk id is the block index, so the stage is found with scalar loads and all
+//     stream base addresses live in SGPRs (lanes add a 32-bit offset).  A persistent grid-stride
+//     variant that stages the table in LDS once per workgroup is kept as an option;
 //   * the three per-stage sums are reduced inside the wavefront with cross-lane shuffles, across
-//     the four wavefronts through LDS, written as one partial per chunk and summed in chunk
-//     order (fp64) by a second tiny kernel, so results do not depend on the grid;
+//     the four wavefronts through LDS, written as one partial per chunk and summed in a fixed
+//     order (fp64) by a second tiny kernel, so results do not depend on the launch shape;
 //   * no matrix cores: there is no contraction anywhere on this path.
 #include <hip/hip_runtime.h>
 
@@ -41,7 +44,7 @@ constexpr int kWaves = kThreads / 64;
 #ifndef FERRET_NT
 #define FERRET_NT 3                 // bit 0: non-temporal loads, bit 1: non-temporal stores
 #endif
-constexpr int kUnroll = FERRET_UNROLL;   // 16-byte vectors per lane per stream in flight
+constexpr int kUnroll = FERRET_UNROLL;   // vectors per lane per stream loaded together when a chunk spans several groups
 constexpr int kUnrolledItersSmall = 4;    // LEVEL 0 kernels: every stage has K' <= 4
 constexpr int kUnrolledItersMid = 8;      // LEVEL 1 kernels: K' <= 8; LEVEL 2 adds the streamed path for any K'
 constexpr int kDefaultResidentCapF32 = 4;   // workgroups per CU, see reserve_lds_for_cap

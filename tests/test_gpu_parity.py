@@ -360,3 +360,39 @@ def test_large_chunks_loop_inside_a_workgroup(chunk):
     _run(w, True, chunk_elems=chunk)
     w16 = W.custom_workload("big_chunks_bf16", [[1_500_000, 77], [300_001]], [3, 1], 4, 2, precision="bf16", seed=75)
     _run(w16, True, chunk_elems=chunk)
+
+
+# ---- checkpoint / resume -----------------------------------------------------------------------------
+@pytest.mark.parametrize("precision", ["f32", "bf16"])
+def test_resume_from_saved_ring_state(precision):
+    """Everything a stage's update path needs to resume is the ring contents, the master and the two
+    integers per stage from ferret_plan_get_state; a fresh plan given those continues bit for bit."""
+    w = W.custom_workload("resume", [[25_000, 16], [7_777]], [2, 1], 3, -1, precision=precision, seed=81)
+    plan_a, st_a, _ = PU.load_workload(w, amplified=True)
+
+    def advance(st, first_step, n):
+        for k in range(first_step, first_step + n):
+            for j in range(2):
+                g = W.draw_grads(w, j, w.stage_numel()[j], amplified=True, step=k)
+                st.set_flat(st.grads, j, g.to(st.storage))
+            st.step(w.lam, w.lr)
+            st.commit()
+
+    advance(st_a, 0, 4)
+    torch.cuda.synchronize()
+    heads, valid = plan_a.get_state()
+    saved_ring = st_a.ring.clone()
+    saved_master = None if st_a.master is None else st_a.master.clone()
+    plan_b = B.plan_for_workload(w)
+    st_b = B.DeviceState(plan_b, PU.tensors_of(w))
+    st_b.ring.copy_(saved_ring)
+    if saved_master is not None:
+        st_b.master.copy_(saved_master)
+    plan_b.set_state(heads, valid)
+    advance(st_a, 4, 3)
+    advance(st_b, 4, 3)
+    torch.cuda.synchronize()
+    assert plan_a.get_state() == plan_b.get_state()
+    assert torch.equal(st_a.ring, st_b.ring)
+    if saved_master is not None:
+        assert torch.equal(st_a.master, st_b.master)
