@@ -144,6 +144,8 @@ def main():
                     help="time the self-tuned-lambda step (all of Alg. 1) instead of the fixed-lambda step")
     ap.add_argument("--accumulate", type=int, default=0, metavar="CA",
                     help="time gradient accumulation (T2): one step = CA arrivals per stage, the last one updates")
+    ap.add_argument("--newest-from-master", action="store_true",
+                    help="bf16 workloads: recompute the newest version from the master instead of reading it")
     ap.add_argument("--graph", action="store_true",
                     help="capture one full ring rotation (ring_depth steps) in a HIP graph and time replays; "
                          "removes the launch overhead that dominates the small workloads")
@@ -173,9 +175,9 @@ def main():
     if args.per_tensor:
         return per_tensor_contrast(w, args, torch, B, W)
     tuning = None
-    if args.blocks_per_cu or args.slot_align or args.slot_skew:
+    if args.blocks_per_cu or args.slot_align or args.slot_skew or args.newest_from_master:
         tuning = dict(blocks_per_cu=args.blocks_per_cu, slot_align_elems=args.slot_align,
-                      slot_skew_elems=args.slot_skew)
+                      slot_skew_elems=args.slot_skew, newest_from_master=int(args.newest_from_master))
     plan = B.plan_for_workload(w, chunk_elems=args.chunk_elems, tuning=tuning)
     st = B.DeviceState(plan, [(n, s) for _, n, s in w.tensors], device=dev, want_grad_out=False,
                        want_norms=not args.no_norms)
@@ -321,7 +323,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "params": w.numel, "stages": w.n_stages, "staleness": w.staleness,
                    "ring_depth": w.ring_depth, "n_iters": w.n_iters, "lambda": w.lam, "lr": w.lr,
-                   "norms": norms, "adaptive_lambda": bool(args.adaptive), "accumulation_steps": args.accumulate, "hip_graph": bool(args.graph),
+                   "norms": norms, "adaptive_lambda": bool(args.adaptive), "accumulation_steps": args.accumulate, "hip_graph": bool(args.graph), "newest_from_master": bool(args.newest_from_master),
                    "chunk_elems": plan.chunk_elems,
                    "algorithmic_bytes_per_step": step_bytes},
         "hbm_gbs_wall": step_bytes / (elapsed / args.steps) / 1e9,

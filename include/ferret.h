@@ -86,6 +86,13 @@ typedef struct {
                                   the stage table staged in LDS; <0: one workgroup per chunk; 0: default */
     int32_t resident_cap;      /* >0: at most this many workgroups resident per CU (enforced by reserving
                                   LDS that the kernel does not use); <0: no cap; 0: default */
+    int32_t newest_from_master; /* FERRET_BF16_MASTER_F32 only.  1: the caller promises that in every stage the
+                                  newest stored version equals the round-to-nearest-even bf16 of the master
+                                  (always true when both come from ferret_push_version with a master and
+                                  ferret_compensate_step); the step then recomputes V[tau] from the master
+                                  instead of reading it (2 bytes per parameter less).  If the promise is
+                                  broken the drifts are taken against the wrong newest version.  0: read it. */
+    int32_t reserved;          /* must be 0 */
 } ferret_tuning;
 
 typedef struct ferret_plan ferret_plan;   /* opaque; host memory; owned by the caller via destroy */

@@ -100,8 +100,16 @@ ferret_status ferret_plan_buckets_tuned(const ferret_tensor *tensors, int32_t n_
         return FERRET_EINVAL;
     }
     int64_t slot_align = kDefaultSlotAlign, slot_skew = 0;
-    int32_t blocks_per_cu = 0, resident_cap = 0;
+    int32_t blocks_per_cu = 0, resident_cap = 0, newest_from_master = 0;
     if (tuning) {
+        if (tuning->reserved != 0) { set_error("plan: tuning.reserved must be 0"); return FERRET_EINVAL; }
+        newest_from_master = tuning->newest_from_master;
+        if (newest_from_master != 0 && newest_from_master != 1) {
+            set_error("plan: newest_from_master = %d, need 0 or 1", newest_from_master); return FERRET_EINVAL;
+        }
+        if (newest_from_master && prec != FERRET_BF16_MASTER_F32) {
+            set_error("plan: newest_from_master only applies to FERRET_BF16_MASTER_F32"); return FERRET_EINVAL;
+        }
         resident_cap = tuning->resident_cap;
         if (resident_cap > 32) { set_error("plan: resident_cap = %d, need <= 32", resident_cap); return FERRET_EINVAL; }
         if (tuning->slot_align_elems) slot_align = tuning->slot_align_elems;
@@ -145,6 +153,7 @@ ferret_status ferret_plan_buckets_tuned(const ferret_tensor *tensors, int32_t n_
     p->chunk_elems = chunk_elems;
     p->blocks_per_cu = blocks_per_cu;
     p->resident_cap = resident_cap;
+    p->newest_from_master = newest_from_master;
 
     // tensors -> stage buckets
     int32_t prev_stage = 0;

@@ -107,6 +107,7 @@ struct ferret_plan {
     int64_t total_params = 0;
     int32_t blocks_per_cu = 0;
     int32_t resident_cap = 0;
+    int32_t newest_from_master = 0;   // bf16: recompute V[tau] from the master instead of reading it
 };
 
 namespace ferret {

@@ -179,6 +179,17 @@ __device__ __forceinline__ void load_master(const char *master, uint32_t vec, v4
     }
 }
 
+// With bf16 storage and the caller's promise that the newest stored version is exactly the
+// round-to-nearest-even bf16 of the master (true whenever both were produced by this library), the
+// newest version need not be read: it is recomputed from the master that is loaded anyway.
+template <typename S>
+__device__ __forceinline__ typename S::Raw newest_from_master(const v4f (&m)[S::kF4]) {
+    float w[S::kElems];
+#pragma unroll
+    for (int q = 0; q < S::kF4; ++q) { w[4 * q] = m[q].x; w[4 * q + 1] = m[q].y; w[4 * q + 2] = m[q].z; w[4 * q + 3] = m[q].w; }
+    return S::narrow(w);
+}
+
 template <typename S, int OUT>
 __device__ __forceinline__ void load_accum(const char *accum, uint32_t vec, v4f (&ac)[S::kF4]) {
     if (OUT & 2) {
@@ -292,13 +303,14 @@ __device__ __forceinline__ void run_chunk(const ChunkPtrs<NV> &p, uint32_t n_vec
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) rg[u] = ld_off<Raw>(p.g, (base + u * kThreads + tid) * RB);
 #pragma unroll
-        for (int s = 0; s < NV; ++s)
+        for (int s = 0; s < NV - ((OUT & 4) ? 1 : 0); ++s)
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) rv[u][s] = ld_off<Raw>(p.v[s], (base + u * kThreads + tid) * RB);
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             load_master<S>(p.master, base + u * kThreads + tid, m[u], !(OUT & 2) || p.acc_update);
             load_accum<S, OUT>(p.accum, base + u * kThreads + tid, ac[u]);
+            if constexpr ((OUT & 4) != 0 && S::kMaster) rv[u][NV - 1] = newest_from_master<S>(m[u]);
         }
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u)
@@ -309,9 +321,10 @@ __device__ __forceinline__ void run_chunk(const ChunkPtrs<NV> &p, uint32_t n_vec
         Raw rg = ld_off<Raw>(p.g, vec * RB), rv[NV];
         v4f m[S::kF4], ac[S::kF4];
 #pragma unroll
-        for (int s = 0; s < NV; ++s) rv[s] = ld_off<Raw>(p.v[s], vec * RB);
+        for (int s = 0; s < NV - ((OUT & 4) ? 1 : 0); ++s) rv[s] = ld_off<Raw>(p.v[s], vec * RB);
         load_master<S>(p.master, vec, m, !(OUT & 2) || p.acc_update);
         load_accum<S, OUT>(p.accum, vec, ac);
+        if constexpr ((OUT & 4) != 0 && S::kMaster) rv[NV - 1] = newest_from_master<S>(m);
         finish_vector<S, NV, COMP, NORMS, OUT>(p, vec, rg, rv, m, ac, lambda, lr, acc);
     }
 }
@@ -330,7 +343,7 @@ __device__ __forceinline__ void run_chunk_streamed(const ChunkPtrs<1> &p, const 
         float g[E], prev[E], cur[E], first[E];
         v4f m[S::kF4], ac[S::kF4];
         Raw rg = ld_off<Raw>(p.g, vec * RB);
-        Raw r0 = ld_off<Raw>(arena + (uint64_t)oldest * slot_bytes, vec * RB);
+        Raw r0 = ld_off<Raw>(arena + (uint64_t)oldest * slot_bytes, vec * RB);      // kp >= 1 here: V[0] is not V[tau]
         load_master<S>(p.master, vec, m, !(OUT & 2) || p.acc_update);
         load_accum<S, OUT>(p.accum, vec, ac);
         S::widen(rg, g);
@@ -347,6 +360,9 @@ __device__ __forceinline__ void run_chunk_streamed(const ChunkPtrs<1> &p, const 
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
                 const uint32_t s_i = (uint32_t)(((uint64_t)(i + b) * tau) / kp);
+                if constexpr ((OUT & 4) != 0 && S::kMaster) {
+                    if (i + b == kp) { r[b] = newest_from_master<S>(m); continue; }
+                }
                 r[b] = ld_off<Raw>(arena + (uint64_t)((oldest + s_i) % R) * slot_bytes, vec * RB);
             }
 #pragma unroll
@@ -361,7 +377,9 @@ __device__ __forceinline__ void run_chunk_streamed(const ChunkPtrs<1> &p, const 
         }
         for (; i <= kp; ++i) {
             const uint32_t s_i = (uint32_t)(((uint64_t)i * tau) / kp);
-            Raw r = ld_off<Raw>(arena + (uint64_t)((oldest + s_i) % R) * slot_bytes, vec * RB);
+            Raw r;
+            if ((OUT & 4) != 0 && S::kMaster && i == kp) r = newest_from_master<S>(m);
+            else r = ld_off<Raw>(arena + (uint64_t)((oldest + s_i) % R) * slot_bytes, vec * RB);
             S::widen(r, cur);
 #pragma unroll
             for (int e = 0; e < E; ++e) {
@@ -846,10 +864,17 @@ static uint32_t reserve_lds_for_cap(const ferret_plan &plan, const StepArgs &a, 
 }
 
 template <typename S, bool PERSISTENT, int LEVEL>
-static hipError_t launch_step_level(const StepArgs &a, bool norms, bool gout, uint32_t grid, uint32_t dyn_lds,
-                                    hipStream_t st) {
+static hipError_t launch_step_level(const StepArgs &a, bool norms, bool gout, bool elide, uint32_t grid,
+                                    uint32_t dyn_lds, hipStream_t st) {
 #define FERRET_LAUNCH(NO, OUT) \
     hipLaunchKernelGGL((step_kernel<S, PERSISTENT, LEVEL, NO, OUT>), dim3(grid), dim3(kThreads), dyn_lds, st, a)
+    if constexpr (S::kMaster && !PERSISTENT) {
+        if (elide) {       // newest version recomputed from the master instead of read
+            if (norms) { if (gout) FERRET_LAUNCH(true, 5); else FERRET_LAUNCH(true, 4); }
+            else       { if (gout) FERRET_LAUNCH(false, 5); else FERRET_LAUNCH(false, 4); }
+            return hipGetLastError();
+        }
+    }
     if (norms) { if (gout) FERRET_LAUNCH(true, 1); else FERRET_LAUNCH(true, 0); }
     else       { if (gout) FERRET_LAUNCH(false, 1); else FERRET_LAUNCH(false, 0); }
 #undef FERRET_LAUNCH
@@ -869,11 +894,11 @@ static hipError_t launch_step_accum(const StepArgs &a, bool norms, bool gout, ui
 }
 
 template <typename S, bool PERSISTENT>
-static hipError_t launch_step_typed(const StepArgs &a, int level, bool norms, bool gout, uint32_t grid,
+static hipError_t launch_step_typed(const StepArgs &a, int level, bool norms, bool gout, bool elide, uint32_t grid,
                                     uint32_t dyn_lds, hipStream_t st) {
-    if (level == 0) return launch_step_level<S, PERSISTENT, 0>(a, norms, gout, grid, dyn_lds, st);
-    if (level == 1) return launch_step_level<S, PERSISTENT, 1>(a, norms, gout, grid, dyn_lds, st);
-    return launch_step_level<S, PERSISTENT, 2>(a, norms, gout, grid, dyn_lds, st);
+    if (level == 0) return launch_step_level<S, PERSISTENT, 0>(a, norms, gout, elide, grid, dyn_lds, st);
+    if (level == 1) return launch_step_level<S, PERSISTENT, 1>(a, norms, gout, elide, grid, dyn_lds, st);
+    return launch_step_level<S, PERSISTENT, 2>(a, norms, gout, elide, grid, dyn_lds, st);
 }
 
 int launch_step(const ferret_plan &plan, const StepArgs &a, float *norms_out, void *stream) {
@@ -897,11 +922,12 @@ int launch_step(const ferret_plan &plan, const StepArgs &a, float *norms_out, vo
         e = plan.prec == FERRET_F32 ? launch_step_accum<F32Store>(a, norms, gout, a.n_chunks, lds, st)
                                     : launch_step_accum<Bf16Store>(a, norms, gout, a.n_chunks, lds, st);
     else if (plan.prec == FERRET_F32)
-        e = persistent ? launch_step_typed<F32Store, true>(a, streamed, norms, gout, grid, lds, st)
-                       : launch_step_typed<F32Store, false>(a, streamed, norms, gout, grid, lds, st);
+        e = persistent ? launch_step_typed<F32Store, true>(a, streamed, norms, gout, false, grid, lds, st)
+                       : launch_step_typed<F32Store, false>(a, streamed, norms, gout, false, grid, lds, st);
     else
-        e = persistent ? launch_step_typed<Bf16Store, true>(a, streamed, norms, gout, grid, lds, st)
-                       : launch_step_typed<Bf16Store, false>(a, streamed, norms, gout, grid, lds, st);
+        e = persistent ? launch_step_typed<Bf16Store, true>(a, streamed, norms, gout, false, grid, lds, st)
+                       : launch_step_typed<Bf16Store, false>(a, streamed, norms, gout, plan.newest_from_master != 0,
+                                                             grid, lds, st);
     if (timed) (void)hipEventRecord(g_prof.stop[g_prof.used++], st);
     if (e != hipSuccess) return (int)e;
     if (norms) {

@@ -396,3 +396,27 @@ def test_resume_from_saved_ring_state(precision):
     assert torch.equal(st_a.ring, st_b.ring)
     if saved_master is not None:
         assert torch.equal(st_a.master, st_b.master)
+
+
+# ---- bf16: newest version recomputed from the master ------------------------------------------------
+@pytest.mark.parametrize("K", [0, 1, 3, -1])
+def test_newest_from_master_gives_identical_results(K):
+    """When the newest stored version is the rounded master (as the generator and the library always
+    make it), skipping its read must not change a single bit; the oracle is the judge of both."""
+    w = W.custom_workload("elide", [[70_000, 40], [30_001], [9_000], [2_048]], [12, 3, 1, 0], 13, K, precision="bf16",
+                          seed=91, lam=0.3)
+    plan_r, st_r, host = PU.load_workload(w, amplified=True, n_iters=K)
+    plan_e, st_e, _ = PU.load_workload(w, amplified=True, n_iters=K, tuning=dict(newest_from_master=1))
+    for st in (st_r, st_e):
+        st.step(w.lam, w.lr)
+    torch.cuda.synchronize()
+    PU.check_step_against_oracle(w, plan_e, st_e, host, K=K)
+    assert torch.equal(st_r.ring, st_e.ring) and torch.equal(st_r.master, st_e.master)
+    assert torch.equal(st_r.grad_out, st_e.grad_out) and torch.equal(st_r.norms, st_e.norms)
+    # and it stays true over further steps, because each step stores the rounding of its new master
+    for k in range(3):
+        for st in (st_r, st_e):
+            st.commit()
+            st.step(w.lam, w.lr, grad_out=False)
+    torch.cuda.synchronize()
+    assert torch.equal(st_r.ring, st_e.ring) and torch.equal(st_r.master, st_e.master)

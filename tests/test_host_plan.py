@@ -188,6 +188,9 @@ BAD_PLANS = [
     dict(tensors=[(10, 0)], n_stages=1, tau=[0], tuning=dict(slot_align_elems=100)),
     dict(tensors=[(10, 0)], n_stages=1, tau=[0], tuning=dict(slot_skew_elems=3)),
     dict(tensors=[(10, 0)], n_stages=1, tau=[0], tuning=dict(resident_cap=33)),
+    dict(tensors=[(10, 0)], n_stages=1, tau=[0], tuning=dict(reserved=1)),
+    dict(tensors=[(10, 0)], n_stages=1, tau=[0], tuning=dict(newest_from_master=1)),      # fp32 plan
+    dict(tensors=[(10, 0)], n_stages=1, tau=[0], prec=1, tuning=dict(newest_from_master=2)),
 ]
 
 
