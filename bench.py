@@ -137,6 +137,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--chunk-elems", type=int, default=0)
     ap.add_argument("--blocks-per-cu", type=int, default=0)
+    ap.add_argument("--resident-cap", type=int, default=0)
     ap.add_argument("--slot-align", type=int, default=0)
     ap.add_argument("--slot-skew", type=int, default=0)
     ap.add_argument("--iters", type=int, default=None, help="override K (-1 = one iteration per version step)")
@@ -144,6 +145,10 @@ def main():
                     help="time the self-tuned-lambda step (all of Alg. 1) instead of the fixed-lambda step")
     ap.add_argument("--accumulate", type=int, default=0, metavar="CA",
                     help="time gradient accumulation (T2): one step = CA arrivals per stage, the last one updates")
+    ap.add_argument("--compensator", default="iter-fisher",
+                    choices=["iter-fisher", "none", "fisher", "step-aware", "gap-aware"],
+                    help="which compensation method the step applies (cost structure of the paper's comparison "
+                         "of compensation methods): iter-fisher = the configured K, none = K 0, fisher = K 1")
     ap.add_argument("--newest-from-master", action="store_true",
                     help="bf16 workloads: recompute the newest version from the master instead of reading it")
     ap.add_argument("--graph", action="store_true",
@@ -172,11 +177,15 @@ def main():
     w = W.make_workload(args.config)
     if args.iters is not None:
         w.n_iters = args.iters
+    if args.compensator in ("none", "step-aware", "gap-aware"):
+        w.n_iters = 0
+    elif args.compensator == "fisher":
+        w.n_iters = 1
     if args.per_tensor:
         return per_tensor_contrast(w, args, torch, B, W)
     tuning = None
-    if args.blocks_per_cu or args.slot_align or args.slot_skew or args.newest_from_master:
-        tuning = dict(blocks_per_cu=args.blocks_per_cu, slot_align_elems=args.slot_align,
+    if args.blocks_per_cu or args.slot_align or args.slot_skew or args.newest_from_master or args.resident_cap:
+        tuning = dict(blocks_per_cu=args.blocks_per_cu, slot_align_elems=args.slot_align, resident_cap=args.resident_cap,
                       slot_skew_elems=args.slot_skew, newest_from_master=int(args.newest_from_master))
     plan = B.plan_for_workload(w, chunk_elems=args.chunk_elems, tuning=tuning)
     st = B.DeviceState(plan, [(n, s) for _, n, s in w.tensors], device=dev, want_grad_out=False,
@@ -226,7 +235,12 @@ def main():
                                          st.norms if norms else None, None, st.workspace if norms else None)
             st.commit()
             return
-        if args.adaptive:
+        if args.compensator in ("step-aware", "gap-aware"):
+            gap = args.compensator == "gap-aware"
+            B.ferret_penalized_step(plan, st.ring, st.grads, st.master, [1.0] * w.n_stages if gap else None,
+                                    [1.0 / (w.lr * w.grad_std)] * w.n_stages if gap else None, w.lr,
+                                    st.norms if norms else None, None, st.workspace if norms else None)
+        elif args.adaptive:
             st.step_adaptive(0.9, 2e-6, w.lr, norms=norms, grad_out=False)
         else:
             st.step(w.lam, w.lr, norms=norms, grad_out=False)
@@ -277,6 +291,10 @@ def main():
     k_avg = statistics.fmean(kernel_ms)
     k_med = statistics.median(kernel_ms)
     per_launch_bytes = step_bytes / args.accumulate if args.accumulate else plan.step_bytes
+    if args.compensator in ("step-aware", "gap-aware") or (args.compensator == "none" and norms):
+        # V[0] is read besides V[tau] (for the gap, or for the weight-gap norm) in stages with staleness
+        elt = 4 if w.precision == "f32" else 2
+        per_launch_bytes += sum(elt * n for n, t in zip(w.stage_numel(), w.staleness) if t >= 1)
     achieved = per_launch_bytes / (k_avg * 1e-3) / 1e9     # the fused step kernel alone
     log(f"step: {ms_per_step * 1e3:.1f} us wall per step; fused kernel avg {k_avg * 1e3:.1f} us, median "
         f"{k_med * 1e3:.1f} us, min {min(kernel_ms) * 1e3:.1f} us -> {achieved:.0f} GB/s algorithmic "
@@ -323,7 +341,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "params": w.numel, "stages": w.n_stages, "staleness": w.staleness,
                    "ring_depth": w.ring_depth, "n_iters": w.n_iters, "lambda": w.lam, "lr": w.lr,
-                   "norms": norms, "adaptive_lambda": bool(args.adaptive), "accumulation_steps": args.accumulate, "hip_graph": bool(args.graph), "newest_from_master": bool(args.newest_from_master),
+                   "norms": norms, "adaptive_lambda": bool(args.adaptive), "accumulation_steps": args.accumulate, "hip_graph": bool(args.graph), "newest_from_master": bool(args.newest_from_master), "compensator": args.compensator,
                    "chunk_elems": plan.chunk_elems,
                    "algorithmic_bytes_per_step": step_bytes},
         "hbm_gbs_wall": step_bytes / (elapsed / args.steps) / 1e9,

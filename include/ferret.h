@@ -108,7 +108,7 @@ typedef struct ferret_plan ferret_plan;   /* opaque; host memory; owned by the c
  *                       maximum staleness of stage j in a P-stage pipeline is P-1-j
  *   n_iters             K >= 0, or FERRET_ITERS_FULL
  *   ring_depth          R >= 1 versions kept per stage, or FERRET_RING_DEPTH_MINIMAL
- *   chunk_elems         0 = default (1024 fp32 / 2048 bf16); otherwise a multiple of 1024, at most 2^24
+ *   chunk_elems         0 = default (2048); otherwise a multiple of 1024, at most 2^24
  *   tuning              NULL or options
  *   out_plan            receives the plan; heads start at slot 0 with no valid version
  */
@@ -270,6 +270,24 @@ typedef struct {
 ferret_status ferret_accumulate_step(const ferret_plan *plan, void *ring, const void *grads, float *master,
                                      const ferret_accumulate *accumulate, float lambda, float lr,
                                      float *norms_out, void *grad_out, void *workspace, void *hip_stream);
+
+/* ---- comparison methods that penalise the step size ------------------------------------------ */
+/* The paper's comparison of compensation methods (Sec. "Comparisons on Gradients Compensation") names
+ * "None", "Fisher", "Step-Aware", "Gap-Aware" beside its own.  "None" is n_iters = 0 and "Fisher"
+ * n_iters = 1 of ferret_compensate_step.  The other two are only named there; the forms offered here
+ * are this library's reading of those published methods, both instances of one update without
+ * iterations,
+ *     theta_next = V[tau] - eta * scale_j * g_0 / (|V[tau] - V[0]| * inv_c_j + 1):
+ *   Step-Aware   scale_j = 1 / max(tau_j, 1), inv_c_j = 0   (step divided by the staleness)
+ *   Gap-Aware    scale_j = 1, inv_c_j = 1 / C_j             (each element's step divided by its gap, the
+ *                distance its weight moved since the stale snapshot in units of a typical step C_j)
+ *   scale, inv_c  host float[n_stages], inv_c >= 0; NULL scale = the Step-Aware values for the plan's
+ *                 current effective staleness, NULL inv_c = zeros
+ * grad_out receives the penalised gradient; norms_out[.][1] equals norms_out[.][0] (no compensation).
+ * Other arguments and the ring protocol (slot written, commit) as in ferret_compensate_step. */
+ferret_status ferret_penalized_step(const ferret_plan *plan, void *ring, const void *grads, float *master,
+                                    const float *scale, const float *inv_c, float lr, float *norms_out,
+                                    void *grad_out, void *workspace, void *hip_stream);
 
 /* ---- misc ------------------------------------------------------------------------------------ */
 const char *ferret_last_error(void);   /* message of the calling thread's last failed call */

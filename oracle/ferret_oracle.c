@@ -290,3 +290,43 @@ int ferret_oracle_accumulate(int64_t n, int32_t n_versions, const void *const *V
     }
     return 0;
 }
+
+/* ==== step-size-penalising comparison methods ============================================
+ *
+ * The paper's comparison of gradient-compensation methods (Sec. "Comparisons on Gradients
+ * Compensation") names two methods that, in its words, mitigate staleness by penalising the
+ * step size of stale gradients, "Step-Aware" and "Gap-Aware", without giving formulas.  The
+ * forms used here (this repository's reading of those published methods, not the paper's):
+ *   Step-Aware   the step of a gradient with staleness tau is divided by tau:
+ *                  theta_next = V[tau] - (eta / max(tau, 1)) * g_0
+ *   Gap-Aware    every element's step is divided by its gap, the distance the weight has moved
+ *                since the stale snapshot measured in units of a typical step size C:
+ *                  G = |V[tau] - V[0]| / C + 1,   theta_next = V[tau] - eta * g_0 / G
+ * Both are the one update
+ *     theta_next = V[tau] - eta * scale * g_0 / (|V[tau] - V[0]| * inv_c + 1)
+ * with (scale, inv_c) = (1/max(tau,1), 0) and (1, 1/C).  No iteration takes place; g_out is the
+ * penalised gradient scale * g_0 / G.  bf16 storage: update on the fp32 master as elsewhere.
+ * Parity status: pinned against closed forms and a hand-worked example; unpinned against the
+ * paper, which prints no formula for these methods.
+ */
+int ferret_oracle_penalized(int64_t n, const void *V0, const void *Vtau, const void *g0, int32_t bf16,
+                            const float *master, double eta, double scale, double inv_c,
+                            void *theta_new, float *master_new, double *g_out)
+{
+    if (n < 0) return -1;
+    for (int64_t e = 0; e < n; ++e) {
+        double newest = widen_at(Vtau, e, bf16);
+        double gap = fabs(newest - widen_at(V0, e, bf16)) * inv_c + 1.0;
+        double g = scale * widen_at(g0, e, bf16) / gap;
+        double base = bf16 ? (double)master[e] : newest;
+        float updated = (float)(base - eta * g);
+        if (g_out) g_out[e] = g;
+        if (bf16) {
+            master_new[e] = updated;
+            ((uint16_t *)theta_new)[e] = ferret_oracle_f32_to_bf16(updated);
+        } else {
+            ((float *)theta_new)[e] = updated;
+        }
+    }
+    return 0;
+}

@@ -74,6 +74,10 @@ def _load():
             ctypes.c_int64, ctypes.c_int32, pp, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32,
             ctypes.c_double, ctypes.c_double, ctypes.c_double, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+        lib.ferret_oracle_penalized.restype = ctypes.c_int
+        lib.ferret_oracle_penalized.argtypes = [
+            ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p,
+            ctypes.c_double, ctypes.c_double, ctypes.c_double, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
         _lib = lib
     return _lib
 
@@ -233,6 +237,27 @@ def accumulate_stage(versions, g0, master, K: int, lam: float, eta: float, scale
         out["new"] = new
         if bf16:
             out["master"] = m_new
+    return out
+
+
+# ---- step-size-penalising comparison methods ------------------------------------------------
+def penalized_stage(V0, Vtau, g0, master, eta: float, scale: float, inv_c: float, bf16: bool = False):
+    """theta_next = V[tau] - eta*scale*g0 / (|V[tau]-V[0]|*inv_c + 1).  Returns dict(new, g[, master])."""
+    dt = np.uint16 if bf16 else np.float32
+    a0, a1, g = _as_np(V0, dt), _as_np(Vtau, dt), _as_np(g0, dt)
+    n = g.size
+    m = _as_np(master, np.float32) if bf16 else None
+    new = np.zeros(n, dt)
+    m_new = np.zeros(n, np.float32) if bf16 else None
+    g_out = np.empty(n, np.float64)
+    rc = _load().ferret_oracle_penalized(n, a0.ctypes.data, a1.ctypes.data, g.ctypes.data, int(bf16),
+                                         m.ctypes.data if bf16 else None, float(eta), float(scale), float(inv_c),
+                                         new.ctypes.data, m_new.ctypes.data if bf16 else None, g_out.ctypes.data)
+    if rc != 0:
+        raise ValueError("ferret_oracle_penalized: bad arguments")
+    out = dict(new=new, g=g_out)
+    if bf16:
+        out["master"] = m_new
     return out
 
 

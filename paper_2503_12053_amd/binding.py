@@ -128,6 +128,7 @@ SIGNATURES = {
     "ferret_pipeline_stage_versions": (c_int32, [_P, c_int32, c_int32]),
     "ferret_pipeline_n_moves": (c_int32, [_P]),
     "ferret_pipeline_move": (c_int32, [_P, c_int32, POINTER(c_int32), POINTER(c_int32), POINTER(c_int32)]),
+    "ferret_penalized_step": (c_int32, [_P, _P, _P, _P, POINTER(c_float), POINTER(c_float), c_float, _P, _P, _P, _P]),
     "ferret_last_error": (c_char_p, []),
     "ferret_version": (c_char_p, []),
     "ferret_copy_bytes": (c_int32, [_P, _P, c_size_t, _P]),
@@ -235,6 +236,16 @@ def ferret_accumulate_step(plan: "Plan", ring, grads, master, accum, scale: floa
     acc = ferret_accumulate(_ptr(accum), scale, mode_arr, st_arr)
     _check(load().ferret_accumulate_step(plan.handle, _ptr(ring), _ptr(grads), _ptr(master), byref(acc), lam, lr,
                                          _ptr(norms_out), _ptr(grad_out), _ptr(workspace), _stream(stream)))
+
+
+def ferret_penalized_step(plan: "Plan", ring, grads, master, scale: Optional[Sequence[float]],
+                          inv_c: Optional[Sequence[float]], lr: float, norms_out=None, grad_out=None, workspace=None,
+                          stream=None) -> None:
+    P = plan.n_stages
+    sc = (c_float * P)(*scale) if scale is not None else None
+    ic = (c_float * P)(*inv_c) if inv_c is not None else None
+    _check(load().ferret_penalized_step(plan.handle, _ptr(ring), _ptr(grads), _ptr(master), sc, ic, lr,
+                                        _ptr(norms_out), _ptr(grad_out), _ptr(workspace), _stream(stream)))
 
 
 def ferret_copy_bytes(dst, src, n_bytes: int, stream=None) -> None:

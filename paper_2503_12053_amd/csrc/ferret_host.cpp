@@ -92,8 +92,9 @@ ferret_status ferret_plan_buckets_tuned(const ferret_tensor *tensors, int32_t n_
     }
     const int64_t vec = vec_elems(prec);
     const int64_t chunk_unit = kThreads * vec;                 // one vector per thread
-    // default (measured best): fp32 one 16-byte vector per lane per stream, bf16 two 8-byte vectors
-    if (chunk_elems == 0) chunk_elems = prec == FERRET_F32 ? chunk_unit : 2 * chunk_unit;
+    // default (measured best on MI355X together with the resident-workgroup cap): two vectors per lane,
+    // i.e. 2048 elements per workgroup for both storage types
+    if (chunk_elems == 0) chunk_elems = 2 * chunk_unit;
     if (chunk_elems < 0 || chunk_elems % chunk_unit != 0 || chunk_elems > (int64_t(1) << 24)) {   // lanes address a chunk with 32-bit byte offsets
         set_error("plan: chunk_elems = %lld, need a positive multiple of %lld up to 2^24", (long long)chunk_elems,
                   (long long)chunk_unit);
@@ -488,6 +489,32 @@ ferret_status ferret_accumulate_step(const ferret_plan *plan, void *ring, const 
     if (err) { set_error("%s: launch failed: %s", who, device_error_string(err)); return FERRET_EDEVICE; }
     for (size_t j = 0; j < P; ++j)
         if (acc->mode[j] == 2) plan->stages[j].step_pending = true;
+    return FERRET_OK;
+}
+
+ferret_status ferret_penalized_step(const ferret_plan *plan, void *ring, const void *grads, float *master,
+                                    const float *scale, const float *inv_c, float lr, float *norms_out,
+                                    void *grad_out, void *workspace, void *hip_stream) {
+    const char *who = "penalized_step";
+    ferret_status rc = check_step_args(who, plan, ring, grads, master, norms_out, grad_out, workspace);
+    if (rc != FERRET_OK) return rc;
+    const size_t P = plan->stages.size();
+    for (size_t j = 0; j < P; ++j) {
+        if (inv_c && !(inv_c[j] >= 0.f)) { set_error("%s: inv_c[%zu] = %g, need >= 0", who, j, (double)inv_c[j]); return FERRET_EINVAL; }
+        if (scale && !(scale[j] == scale[j])) { set_error("%s: scale[%zu] is NaN", who, j); return FERRET_EINVAL; }
+    }
+    StepArgs a;
+    fill_step_args(plan, a, ring, grads, master, 0.f, lr, norms_out, grad_out, workspace);
+    a.penalized = 1;
+    for (size_t j = 0; j < P; ++j) {
+        const int32_t tau = a.stage[j].tau;
+        a.stage[j].kp = 0;                                   // no iterations
+        a.pen_scale[j] = scale ? scale[j] : 1.0f / (float)(tau > 1 ? tau : 1);
+        a.pen_inv_c[j] = inv_c ? inv_c[j] : 0.f;
+    }
+    int err = launch_step(*plan, a, norms_out, hip_stream);
+    if (err) { set_error("%s: launch failed: %s", who, device_error_string(err)); return FERRET_EDEVICE; }
+    for (const Stage &s : plan->stages) s.step_pending = true;
     return FERRET_OK;
 }
 

@@ -55,14 +55,16 @@ struct StepArgs {
     // gradient accumulation (null for the plain step)
     float *accum;        // fp32 flat buffer: running sum of compensated gradients
     float accum_scale;   // factor on the sum at the update
-    uint32_t pad2_;
+    uint32_t penalized;  // 1: step-size-penalising comparison method (pen_scale / pen_inv_c per stage)
     uint8_t mode[FERRET_MAX_STAGES];   // per stage: 0 skip, 1 accumulate only, 2 accumulate + update
     // chunk_begin of every stage again, densely packed (unused entries = UINT32_MAX), so that a
     // workgroup can find its chunk's stage with a few wide scalar loads
     uint32_t chunk_begin[FERRET_MAX_STAGES];
+    float pen_scale[FERRET_MAX_STAGES];
+    float pen_inv_c[FERRET_MAX_STAGES];
     StageDesc stage[FERRET_MAX_STAGES];
 };
-static_assert(sizeof(StepArgs) <= 3600, "StepArgs must fit the kernel-argument segment");
+static_assert(sizeof(StepArgs) + 16 <= 4096, "StepArgs (+ one pointer) must fit the 4 KiB kernel-argument segment");
 
 struct PushArgs {
     void *ring;

@@ -47,8 +47,7 @@ constexpr int kWaves = kThreads / 64;
 constexpr int kUnroll = FERRET_UNROLL;   // vectors per lane per stream loaded together when a chunk spans several groups
 constexpr int kUnrolledItersSmall = 4;    // LEVEL 0 kernels: every stage has K' <= 4
 constexpr int kUnrolledItersMid = 8;      // LEVEL 1 kernels: K' <= 8; LEVEL 2 adds the streamed path for any K'
-constexpr int kDefaultResidentCapF32 = 4;   // workgroups per CU, see reserve_lds_for_cap
-constexpr int kDefaultResidentCapBf16 = 3;
+constexpr int kStreamBatch = 8;           // boundaries the streamed path loads together
 constexpr uint64_t kCapThresholdBytes = 512ull << 20;
 
 // 16-byte vectors as clang vector types (so that the non-temporal builtins accept them)
@@ -160,6 +159,7 @@ struct ChunkPtrs {
     char *accum;                    // fp32 running sum of compensated gradients (accumulation kernels)
     float acc_scale;                // factor applied to the sum at the update
     bool acc_update;                // this arrival completes the group: update and clear the sum
+    float pen_scale, pen_inv_c;     // step-size penalty of the comparison methods (OUT & 8)
 };
 
 template <typename T>
@@ -201,11 +201,15 @@ __device__ __forceinline__ void load_accum(const char *accum, uint32_t vec, v4f 
 // theta_next = V[tau] - eta * g (fp32 storage), or master - eta * g with the stored version its
 // round-to-nearest-even bf16; then the stores of one lane-vector.
 template <typename S, int NV, int OUT>
-__device__ __forceinline__ void update_and_store(const ChunkPtrs<NV> &p, uint32_t vec, const float (&g)[S::kElems],
-                                                 const float (&newest)[S::kElems], const v4f (&m_in)[S::kF4],
-                                                 const v4f (&ac_in)[S::kF4], float lr) {
+__device__ __forceinline__ void update_and_store(const ChunkPtrs<NV> &p, uint32_t vec, float (&g)[S::kElems],
+                                                 const float (&newest)[S::kElems], const float (&first)[S::kElems],
+                                                 const v4f (&m_in)[S::kF4], const v4f (&ac_in)[S::kF4], float lr) {
     constexpr int E = S::kElems;
     constexpr uint32_t kF32Bytes = E * 4;
+    if (OUT & 8) {          // comparison methods: shrink the step by scale / (|V[tau]-V[0]| / C + 1)
+#pragma unroll
+        for (int e = 0; e < E; ++e) g[e] = p.pen_scale * g[e] / fmaf(fabsf(newest[e] - first[e]), p.pen_inv_c, 1.0f);
+    }
     if (OUT & 1) {
 #pragma unroll
         for (int q = 0; q < S::kF4; ++q)
@@ -280,7 +284,7 @@ __device__ __forceinline__ void finish_vector(const ChunkPtrs<NV> &p, uint32_t v
             acc[2] = fmaf(gap, gap, acc[2]);
         }
     }
-    update_and_store<S, NV, OUT>(p, vec, g, prev, m_in, ac_in, lr);
+    update_and_store<S, NV, OUT>(p, vec, g, prev, first, m_in, ac_in, lr);
 }
 
 // A chunk with a compile-time number NV of versions to read.  Groups of kThreads*kUnroll vectors
@@ -329,7 +333,7 @@ __device__ __forceinline__ void run_chunk(const ChunkPtrs<NV> &p, uint32_t n_vec
     }
 }
 
-// Any number of versions (K' > 8): stream them, four boundaries at a time.  `arena` points at this
+// Any number of versions (K' > 8): stream them, kStreamBatch boundaries at a time.  `arena` points at this
 // chunk's first element in slot 0 of the stage; slots are slot_bytes apart.
 template <typename S, bool NORMS, int OUT>
 __device__ __forceinline__ void run_chunk_streamed(const ChunkPtrs<1> &p, const char *arena, uint64_t slot_bytes,
@@ -354,37 +358,25 @@ __device__ __forceinline__ void run_chunk_streamed(const ChunkPtrs<1> &p, const 
 #pragma unroll
             for (int e = 0; e < E; ++e) acc[0] = fmaf(g[e], g[e], acc[0]);
         }
-        uint32_t i = 1;
-        for (; i + 3 <= kp; i += 4) {           // four boundaries at a time: their loads overlap
-            Raw r[4];
+        for (uint32_t i = 1; i <= kp; i += kStreamBatch) {     // a batch of boundaries at a time: their loads overlap
+            const uint32_t count = kp - i + 1 < (uint32_t)kStreamBatch ? kp - i + 1 : (uint32_t)kStreamBatch;   // uniform
+            Raw r[kStreamBatch];
 #pragma unroll
-            for (int b = 0; b < 4; ++b) {
+            for (int b = 0; b < kStreamBatch; ++b) {
+                if ((uint32_t)b >= count) break;
                 const uint32_t s_i = (uint32_t)(((uint64_t)(i + b) * tau) / kp);
-                if constexpr ((OUT & 4) != 0 && S::kMaster) {
-                    if (i + b == kp) { r[b] = newest_from_master<S>(m); continue; }
-                }
-                r[b] = ld_off<Raw>(arena + (uint64_t)((oldest + s_i) % R) * slot_bytes, vec * RB);
+                if ((OUT & 4) != 0 && S::kMaster && i + b == kp) r[b] = newest_from_master<S>(m);
+                else r[b] = ld_off<Raw>(arena + (uint64_t)((oldest + s_i) % R) * slot_bytes, vec * RB);
             }
 #pragma unroll
-            for (int b = 0; b < 4; ++b) {
+            for (int b = 0; b < kStreamBatch; ++b) {
+                if ((uint32_t)b >= count) break;
                 S::widen(r[b], cur);
 #pragma unroll
                 for (int e = 0; e < E; ++e) {
                     g[e] = approximator(g[e], lambda, cur[e], prev[e]);
                     prev[e] = cur[e];
                 }
-            }
-        }
-        for (; i <= kp; ++i) {
-            const uint32_t s_i = (uint32_t)(((uint64_t)i * tau) / kp);
-            Raw r;
-            if ((OUT & 4) != 0 && S::kMaster && i == kp) r = newest_from_master<S>(m);
-            else r = ld_off<Raw>(arena + (uint64_t)((oldest + s_i) % R) * slot_bytes, vec * RB);
-            S::widen(r, cur);
-#pragma unroll
-            for (int e = 0; e < E; ++e) {
-                g[e] = approximator(g[e], lambda, cur[e], prev[e]);
-                prev[e] = cur[e];
             }
         }
         if (NORMS) {
@@ -395,7 +387,7 @@ __device__ __forceinline__ void run_chunk_streamed(const ChunkPtrs<1> &p, const 
                 acc[2] = fmaf(gap, gap, acc[2]);
             }
         }
-        update_and_store<S, 1, OUT>(p, vec, g, prev, m, ac, lr);
+        update_and_store<S, 1, OUT>(p, vec, g, prev, first, m, ac, lr);
     }
 }
 
@@ -461,6 +453,8 @@ __device__ __forceinline__ void do_chunk(const StepArgs &a, const ChunkInfo &c, 
     p.accum = (OUT & 2) ? reinterpret_cast<char *>(a.accum) + c.flat_elem0 * 4 : nullptr;
     p.acc_scale = a.accum_scale;
     p.acc_update = c.acc_update;
+    p.pen_scale = (OUT & 8) ? a.pen_scale[c.stage] : 1.f;
+    p.pen_inv_c = (OUT & 8) ? a.pen_inv_c[c.stage] : 0.f;
     run_chunk<S, NV, COMP, NORMS, OUT>(p, c.n_vecs, lambda, a.lr, acc);
 }
 
@@ -483,7 +477,7 @@ __device__ __forceinline__ void process_chunk(const StepArgs &a, const ChunkInfo
     // versions to read: the K'+1 boundaries; with K' = 0 only V[tau], plus V[0] when the weight
     // gap is wanted for the norms
     if (c.kp == 0) {
-        if (NORMS && c.tau > 0) do_chunk<S, 2, false, NORMS, OUT>(a, c, lambda, acc);
+        if ((NORMS || (OUT & 8)) && c.tau > 0) do_chunk<S, 2, false, NORMS, OUT>(a, c, lambda, acc);
         else do_chunk<S, 1, false, NORMS, OUT>(a, c, lambda, acc);
     } else if (c.kp == 1) {
         do_chunk<S, 2, true, NORMS, OUT>(a, c, lambda, acc);
@@ -512,6 +506,8 @@ __device__ __forceinline__ void process_chunk(const StepArgs &a, const ChunkInfo
         p.accum = (OUT & 2) ? reinterpret_cast<char *>(a.accum) + c.flat_elem0 * 4 : nullptr;
         p.acc_scale = a.accum_scale;
         p.acc_update = c.acc_update;
+        p.pen_scale = 1.f;
+        p.pen_inv_c = 0.f;
         run_chunk_streamed<S, NORMS, OUT>(p, c.arena, c.slot_bytes, c.R, c.head, c.tau, c.kp, c.n_vecs,
                                            lambda, a.lr, acc);
     }
@@ -836,24 +832,57 @@ static uint32_t grid_for(const ferret_plan &plan, uint32_t n_chunks, int *err) {
     return g < n_chunks ? (uint32_t)g : n_chunks;
 }
 
-// Resident-workgroup cap.  Measured on MI355X: this read-mostly mix of 6-7 streams peaks when a CU
-// holds roughly 100 KB of requests in flight and loses a few per cent beyond that, so the launch
-// reserves LDS the kernel never touches: with 160 KiB of LDS per CU, asking for
-// floor(160 KiB / cap) bytes per workgroup lets exactly `cap` of them be resident.
+// Resident-workgroup cap.  Measured on MI355X: for steps that stream far more than the 256 MB
+// memory-side cache holds, throughput depends on how many workgroups a CU holds at once, with a sharp
+// optimum that moves with the traffic of one chunk: at the default 2048-element chunks the best count is
+// 6 for K' = 0, 4 for K' = 1, 3 for K' = 2..4, 2 beyond (and 3 for bf16 at K' = 4); one too few costs
+// 5-10 %, one too many 2-5 %.  ceil(128 KiB / bytes one chunk moves) reproduces those counts (K' = 2 gets
+// 4 instead of 3).  The launch enforces the count by reserving LDS the kernel never touches: with 160 KiB
+// of LDS per CU, asking for floor(160 KiB / cap) bytes per workgroup lets exactly `cap` of them be resident.
 constexpr uint32_t kLdsPerCu = 160u * 1024u;
 constexpr uint32_t kLdsPerBlockMax = 64u * 1024u;
+constexpr uint64_t kInFlightTargetBytes = 128u * 1024u;
 
 static uint32_t reserve_lds_for_cap(const ferret_plan &plan, const StepArgs &a, bool persistent) {
     int32_t cap = plan.resident_cap;
     if (cap == 0) {
-        // default: cap only steps whose traffic is far beyond the 256 MB memory-side cache; steps
-        // that run out of that cache are latency-bound instead and want every wave they can get
+        // default: cap only steps whose traffic is far beyond the memory-side cache; steps that run out
+        // of that cache are latency-bound instead and want every wave they can get
+        // Bytes one lane-vector's worth of a chunk has in flight at once, per element, for each stage; the
+        // cap is taken from the stage at the traffic-weighted median, because workgroups are dispatched in
+        // chunk order and mostly one stage's chunks are resident at a time.
         const uint64_t sb = plan.prec == FERRET_F32 ? 4 : 2;
-        uint64_t bytes = 0;
-        for (uint32_t j = 0; j < a.n_stages; ++j)
-            bytes += a.stage[j].n_elems * (sb * (a.stage[j].kp + 3u) + (plan.prec == FERRET_F32 ? 0u : 8u));
-        cap = bytes > kCapThresholdBytes ? (plan.prec == FERRET_F32 ? kDefaultResidentCapF32 : kDefaultResidentCapBf16)
-                                         : -1;
+        uint64_t total = 0;
+        uint64_t per_elem[FERRET_MAX_STAGES], traffic[FERRET_MAX_STAGES];
+        uint32_t order[FERRET_MAX_STAGES], n = 0;
+        for (uint32_t j = 0; j < a.n_stages; ++j) {
+            if (a.accum && a.mode[j] == 0) continue;
+            const uint32_t kp = a.stage[j].kp;
+            // versions loaded together: all K'+1 on the unrolled paths, V[0] plus a batch on the streamed one
+            const uint32_t versions = kp <= (uint32_t)kUnrolledItersMid ? kp + 1u : 1u + kStreamBatch;
+            uint64_t per = sb * (versions + 2u) + (plan.prec == FERRET_F32 ? 0u : 8u);
+            if (kp == 0 && a.stage[j].tau > 0 && (a.partials || a.penalized)) per += sb;   // V[0] for the gap
+            if (a.accum) per += 8 - sb;     // running sum read + written; most arrivals write no version (measured: 3 at K' = 3)
+            per_elem[n] = per;
+            traffic[n] = a.stage[j].n_elems * (sb * (kp + 3u) + (plan.prec == FERRET_F32 ? 0u : 8u));
+            total += traffic[n];
+            order[n] = n;
+            ++n;
+        }
+        if (total <= kCapThresholdBytes || n == 0) return 0;
+        for (uint32_t i = 1; i < n; ++i)                      // insertion sort by bytes per element
+            for (uint32_t k = i; k > 0 && per_elem[order[k]] < per_elem[order[k - 1]]; --k) {
+                const uint32_t t = order[k]; order[k] = order[k - 1]; order[k - 1] = t;
+            }
+        uint64_t seen = 0, median_per = per_elem[order[n - 1]];
+        for (uint32_t i = 0; i < n; ++i) {
+            seen += traffic[order[i]];
+            if (2 * seen >= total) { median_per = per_elem[order[i]]; break; }
+        }
+        const uint64_t block_bytes = (uint64_t)a.chunk_elems * median_per;
+        cap = (int32_t)((kInFlightTargetBytes + block_bytes - 1) / block_bytes);
+        if (cap < 2) cap = 2;
+        if (cap >= 8) return 0;                               // 8 fit anyway
     }
     if (cap <= 0) return 0;
     const uint32_t used = (persistent ? (uint32_t)sizeof(StageDesc) * FERRET_MAX_STAGES : 0u) + 64u;
@@ -877,6 +906,18 @@ static hipError_t launch_step_level(const StepArgs &a, bool norms, bool gout, bo
     }
     if (norms) { if (gout) FERRET_LAUNCH(true, 1); else FERRET_LAUNCH(true, 0); }
     else       { if (gout) FERRET_LAUNCH(false, 1); else FERRET_LAUNCH(false, 0); }
+#undef FERRET_LAUNCH
+    return hipGetLastError();
+}
+
+// Launches of the step-size-penalising comparison methods: no iterations, so the smallest kernel level.
+template <typename S>
+static hipError_t launch_step_penalized(const StepArgs &a, bool norms, bool gout, uint32_t grid, uint32_t dyn_lds,
+                                        hipStream_t st) {
+#define FERRET_LAUNCH(NO, OUT) \
+    hipLaunchKernelGGL((step_kernel<S, false, 0, NO, OUT>), dim3(grid), dim3(kThreads), dyn_lds, st, a)
+    if (norms) { if (gout) FERRET_LAUNCH(true, 9); else FERRET_LAUNCH(true, 8); }
+    else       { if (gout) FERRET_LAUNCH(false, 9); else FERRET_LAUNCH(false, 8); }
 #undef FERRET_LAUNCH
     return hipGetLastError();
 }
@@ -915,10 +956,13 @@ int launch_step(const ferret_plan &plan, const StepArgs &a, float *norms_out, vo
     const bool norms = norms_out != nullptr, gout = a.grad_out != nullptr;
     const bool timed = g_prof.on && g_prof.used < (int32_t)g_prof.start.size();
     if (timed) (void)hipEventRecord(g_prof.start[g_prof.used], st);
-    const bool persistent = grid < a.n_chunks && !a.accum;
+    const bool persistent = grid < a.n_chunks && !a.accum && !a.penalized;
     const uint32_t lds = reserve_lds_for_cap(plan, a, persistent);
     hipError_t e;
-    if (a.accum)
+    if (a.penalized)
+        e = plan.prec == FERRET_F32 ? launch_step_penalized<F32Store>(a, norms, gout, a.n_chunks, lds, st)
+                                    : launch_step_penalized<Bf16Store>(a, norms, gout, a.n_chunks, lds, st);
+    else if (a.accum)
         e = plan.prec == FERRET_F32 ? launch_step_accum<F32Store>(a, norms, gout, a.n_chunks, lds, st)
                                     : launch_step_accum<Bf16Store>(a, norms, gout, a.n_chunks, lds, st);
     else if (plan.prec == FERRET_F32)
