@@ -13,10 +13,10 @@
 //   * every operand is touched exactly once, with 128-bit (fp32) / 64-bit (bf16) non-temporal
 //     accesses; consecutive lanes of a 64-wide wavefront touch consecutive vectors, so every
 //     access of a wavefront is one contiguous run of memory;
-//   * one workgroup of 256 lanes per chunk of 1024 fp32 / 2048 bf16 elements: all loads of a chunk
-//     (gradient + K'+1 versions) are issued before the first arithmetic, and the hardware
-//     dispatcher balances the load; a cap on resident workgroups per CU (unused LDS) keeps the
-//     bytes in flight at the measured optimum for large steps;
+//   * one workgroup of 256 lanes per chunk of 2048 elements (two vectors per lane, one after the
+//     other): all loads of a vector (gradient + K'+1 versions) are issued before the first
+//     arithmetic, and the hardware dispatcher balances the load; a cap on resident workgroups per
+//     CU (unused LDS) keeps the traffic in flight at the measured optimum for large steps;
 //   * a stage's tensors are one flat bucket; the stage table (48 B per stage) arrives as a kernel
 //     argument; the chunk id is the block index, so the stage is found with scalar loads and all
 //     stream base addresses live in SGPRs (lanes add a 32-bit offset).  A persistent grid-stride
@@ -836,12 +836,12 @@ static uint32_t grid_for(const ferret_plan &plan, uint32_t n_chunks, int *err) {
 // memory-side cache holds, throughput depends on how many workgroups a CU holds at once, with a sharp
 // optimum that moves with the traffic of one chunk: at the default 2048-element chunks the best count is
 // 6 for K' = 0, 4 for K' = 1, 3 for K' = 2..4, 2 beyond (and 3 for bf16 at K' = 4); one too few costs
-// 5-10 %, one too many 2-5 %.  ceil(128 KiB / bytes one chunk moves) reproduces those counts (K' = 2 gets
-// 4 instead of 3).  The launch enforces the count by reserving LDS the kernel never touches: with 160 KiB
+// 5-10 %, one too many 2-5 %.  ceil(120 KiB / bytes one chunk moves) reproduces those counts (K' = 0
+// without norms gets 5 instead of 6).  The launch enforces the count by reserving LDS the kernel never touches: with 160 KiB
 // of LDS per CU, asking for floor(160 KiB / cap) bytes per workgroup lets exactly `cap` of them be resident.
 constexpr uint32_t kLdsPerCu = 160u * 1024u;
 constexpr uint32_t kLdsPerBlockMax = 64u * 1024u;
-constexpr uint64_t kInFlightTargetBytes = 128u * 1024u;
+constexpr uint64_t kInFlightTargetBytes = 120u * 1024u;
 
 static uint32_t reserve_lds_for_cap(const ferret_plan &plan, const StepArgs &a, bool persistent) {
     int32_t cap = plan.resident_cap;

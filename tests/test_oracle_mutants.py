@@ -14,7 +14,8 @@ import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SRC = os.path.join(ROOT, "oracle", "ferret_oracle.c")
-PINS = ["tests/test_oracle_pins.py", "tests/test_oracle_lambda_pins.py", "tests/test_oracle_accumulate_pins.py"]
+PINS = ["tests/test_oracle_pins.py", "tests/test_oracle_lambda_pins.py", "tests/test_oracle_accumulate_pins.py",
+        "tests/test_oracle_penalized_pins.py"]
 
 MUTANTS = [
     ("square of the original gradient instead of the current iterate",
@@ -63,6 +64,14 @@ MUTANTS = [
      "        accum_out[e] = 0.0f;", "        accum_out[e] = (float)total;"),
     ("scale not applied", None, None,
      "        float updated = (float)(base - eta * scale * total);", "        float updated = (float)(base - eta * total);"),
+    ("gap taken with its sign", None, None,
+     "        double gap = fabs(newest - widen_at(V0, e, bf16)) * inv_c + 1.0;",
+     "        double gap = (newest - widen_at(V0, e, bf16)) * inv_c + 1.0;"),
+    ("gap without the + 1", None, None,
+     "        double gap = fabs(newest - widen_at(V0, e, bf16)) * inv_c + 1.0;",
+     "        double gap = fabs(newest - widen_at(V0, e, bf16)) * inv_c;"),
+    ("penalty multiplies instead of divides", None, None,
+     "        double g = scale * widen_at(g0, e, bf16) / gap;", "        double g = scale * widen_at(g0, e, bf16) * gap;"),
 ]
 
 
@@ -102,8 +111,9 @@ def test_pins_catch_mutant(tmp_path, name, pre_old, pre_new, old, new):
     _build(src, lib)
     # run the pin file of the mutated block first (cheap); any failing pin is enough
     site = src.index(new)
-    first = PINS[2] if site > src.index("==== gradient accumulation") else (
-        PINS[1] if site > src.index("==== adaptive lambda") else PINS[0])
+    first = PINS[3] if site > src.index("==== step-size-penalising") else (
+        PINS[2] if site > src.index("==== gradient accumulation") else (
+            PINS[1] if site > src.index("==== adaptive lambda") else PINS[0]))
     r = _run_pins(lib, [first])
     if r.returncode == 0:
         r = _run_pins(lib)
