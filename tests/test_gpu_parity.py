@@ -420,3 +420,25 @@ def test_newest_from_master_gives_identical_results(K):
             st.step(w.lam, w.lr, grad_out=False)
     torch.cuda.synchronize()
     assert torch.equal(st_r.ring, st_e.ring) and torch.equal(st_r.master, st_e.master)
+
+
+# ---- many small random configurations ------------------------------------------------------------------
+@pytest.mark.parametrize("seed", range(24))
+def test_random_configurations(seed):
+    """Random stage counts, tensor sizes (ragged on purpose), staleness, ring depth, iteration count,
+    storage type, chunk size and launch shape, each compared with the oracle."""
+    rng = np.random.default_rng(1000 + seed)
+    n_stages = int(rng.integers(1, 7))
+    R = int(rng.integers(1, 10))
+    tau = [int(rng.integers(0, R)) for _ in range(n_stages)]
+    sizes = [[int(rng.choice([1, 7, 8, 9, 63, 500, 1024, 2047, 2049, 5000, 30_000]) * rng.integers(1, 4))
+              for _ in range(int(rng.integers(1, 5)))] for _ in range(n_stages)]
+    K = int(rng.choice([-1, 0, 1, 2, 3, 5, 9]))
+    precision = "bf16" if seed % 2 else "f32"
+    depth = B.FERRET_RING_DEPTH_MINIMAL if seed % 5 == 0 else R
+    chunk = int(rng.choice([0, 1024, 3072, 8192]))
+    tuning = [None, dict(blocks_per_cu=2), dict(resident_cap=2), dict(blocks_per_cu=-1, resident_cap=-1)][seed % 4]
+    w = W.custom_workload(f"random{seed}", sizes, tau, R, K, precision=precision, seed=2000 + seed,
+                          lam=float(rng.choice([0.1, 0.5, -0.3])), lr=float(rng.choice([0.01, 0.2])))
+    heads = [int(rng.integers(0, 16)) for _ in range(n_stages)]
+    _run(w, True, chunk_elems=chunk, tuning=tuning, ring_depth=depth, n_iters=K, heads=heads)
