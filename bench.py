@@ -143,6 +143,8 @@ def main():
     ap.add_argument("--iters", type=int, default=None, help="override K (-1 = one iteration per version step)")
     ap.add_argument("--adaptive", action="store_true",
                     help="time the self-tuned-lambda step (all of Alg. 1) instead of the fixed-lambda step")
+    ap.add_argument("--adaptive-fused", action="store_true",
+                    help="as --adaptive, but in one pass: each lambda step takes effect one call later than in Alg. 1")
     ap.add_argument("--accumulate", type=int, default=0, metavar="CA",
                     help="time gradient accumulation (T2): one step = CA arrivals per stage, the last one updates")
     ap.add_argument("--compensator", default="iter-fisher",
@@ -207,14 +209,23 @@ def main():
         f"(inputs ready in {time.perf_counter() - t0:.1f} s)")
 
     norms = not args.no_norms
+    fused_extra = 0
+    if args.adaptive_fused:
+        args.adaptive = True
     if args.adaptive:
         # Alg. 1 with eta_lambda > 0: lambda_j starts at lambda0, averages at zero; the paper's run
         # uses a small lambda learning rate (its "mu" = 2e-6)
         st.enable_adaptive(w.lam)
         elt = 4 if w.precision == "f32" else 2
         state_bytes = sum((3 * elt + 16) * n for n, t in zip(w.stage_numel(), w.staleness) if t >= 1)
+        if args.adaptive_fused:
+            # in one pass g_0 and V[0] are read once; V[1] is extra only where it is not a segment boundary
+            kp = [plan.stage_effective_iters(j) for j in range(w.n_stages)]
+            state_bytes = sum((16 + (0 if t // k == 1 else elt)) * n
+                              for n, t, k in zip(w.stage_numel(), w.staleness, kp) if t >= 1)
+            fused_extra = state_bytes
         step_bytes += state_bytes
-        log(f"adaptive lambda: state pass adds {state_bytes} algorithmic bytes per step")
+        log(f"adaptive lambda: the lambda block adds {state_bytes} algorithmic bytes per step")
 
     accum = None
     if args.accumulate:
@@ -241,7 +252,7 @@ def main():
                                     [1.0 / (w.lr * w.grad_std)] * w.n_stages if gap else None, w.lr,
                                     st.norms if norms else None, None, st.workspace if norms else None)
         elif args.adaptive:
-            st.step_adaptive(0.9, 2e-6, w.lr, norms=norms, grad_out=False)
+            st.step_adaptive(0.9, 2e-6, w.lr, norms=norms, grad_out=False, fused=args.adaptive_fused)
         else:
             st.step(w.lam, w.lr, norms=norms, grad_out=False)
         st.commit()
@@ -290,7 +301,7 @@ def main():
     params_per_s = w.numel / (elapsed / args.steps)
     k_avg = statistics.fmean(kernel_ms)
     k_med = statistics.median(kernel_ms)
-    per_launch_bytes = step_bytes / args.accumulate if args.accumulate else plan.step_bytes
+    per_launch_bytes = step_bytes / args.accumulate if args.accumulate else plan.step_bytes + fused_extra
     if args.compensator in ("step-aware", "gap-aware") or (args.compensator == "none" and norms):
         # V[0] is read besides V[tau] (for the gap, or for the weight-gap norm) in stages with staleness
         elt = 4 if w.precision == "f32" else 2
@@ -341,7 +352,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "params": w.numel, "stages": w.n_stages, "staleness": w.staleness,
                    "ring_depth": w.ring_depth, "n_iters": w.n_iters, "lambda": w.lam, "lr": w.lr,
-                   "norms": norms, "adaptive_lambda": bool(args.adaptive), "accumulation_steps": args.accumulate, "hip_graph": bool(args.graph), "newest_from_master": bool(args.newest_from_master), "compensator": args.compensator,
+                   "norms": norms, "adaptive_lambda": ("one-pass" if args.adaptive_fused else bool(args.adaptive)), "accumulation_steps": args.accumulate, "hip_graph": bool(args.graph), "newest_from_master": bool(args.newest_from_master), "compensator": args.compensator,
                    "chunk_elems": plan.chunk_elems,
                    "algorithmic_bytes_per_step": step_bytes},
         "hbm_gbs_wall": step_bytes / (elapsed / args.steps) / 1e9,

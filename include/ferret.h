@@ -229,13 +229,24 @@ ferret_status ferret_compensate_step(const ferret_plan *plan, void *ring, const 
  * inner products go through it before the norms do).  FERRET_EINVAL if the plan has n_iters = 0.
  * Implementation: one pass over g_0, v_r, v_a, V[0], V[1] that forms the two sums and the new
  * averages (28 bytes per fp32 parameter), a tiny kernel that steps lambda, then the same fused
- * kernel as ferret_compensate_step reading lambda_j from device memory. */
+ * kernel as ferret_compensate_step reading lambda_j from device memory.
+ *   fused        0: the order above, which is Alg. 1's (two passes over the gradient).
+ *                1: ONE pass.  The lambda block needs two sums over the whole stage before its result
+ *                can scale anything, so a single pass cannot use the new lambda_j; instead the
+ *                iterations of this call use lambda_j as it is BEFORE the call and lambda_j takes its
+ *                step afterwards, i.e. every lambda step acts one call later than in Alg. 1.  The
+ *                sequence of lambda_j, v_r, v_a for given gradients and versions is unchanged; with
+ *                the paper's eta_lambda (about 1e-6) consecutive lambda_j differ in the sixth digit.
+ *                Moves 16 + one stored version fewer bytes per parameter than the two passes.
+ *   reserved     must be 0 */
 typedef struct {
     float *lambda;
     float *v_r;
     float *v_a;
     float alpha;
     float eta_lambda;
+    int32_t fused;
+    int32_t reserved;
 } ferret_adaptive;
 
 ferret_status ferret_compensate_step_adaptive(const ferret_plan *plan, void *ring, const void *grads,

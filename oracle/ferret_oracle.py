@@ -190,9 +190,14 @@ def lambda_update(g0, V0, V1, lam: float, alpha: float, eta_lambda: float, v_r, 
 
 
 def compensate_stage_adaptive(versions, g0, master, K: int, lam: float, alpha: float, eta_lambda: float,
-                              eta: float, v_r, v_a, bf16: bool = False, n_threads: int = 1):
+                              eta: float, v_r, v_a, bf16: bool = False, n_threads: int = 1,
+                              lambda_step_last: bool = False):
     """All of Alg. 1 for one stage: lambda block (skipped when eta_lambda = 0 or tau = 0), then the
-    iterations with the NEW lambda, then the update.  Returns a dict."""
+    iterations with the NEW lambda, then the update.  Returns a dict.
+
+    lambda_step_last = True is the one-pass ordering the library offers beside Alg. 1's: the same lambda
+    block on the same inputs, but the iterations of this call still use the lambda passed in, so that each
+    lambda step takes effect one call later."""
     tau = len(versions) - 1
     if eta_lambda > 0 and tau >= 1:
         lam_new, r_new, a_new, sums = lambda_update(g0, versions[0], versions[1], lam, alpha, eta_lambda,
@@ -201,11 +206,12 @@ def compensate_stage_adaptive(versions, g0, master, K: int, lam: float, alpha: f
         lam_new, sums = float(lam), np.zeros(2)
         r_new, a_new = _as_np(v_r, np.float32).copy(), _as_np(v_a, np.float32).copy()
     out = dict(lam=lam_new, v_r=r_new, v_a=a_new, sums=sums)
+    lam_used = float(lam) if lambda_step_last else lam_new
     if bf16:
-        new, m_new, g_out, norms = compensate_stage_bf16(versions, g0, master, K, lam_new, eta, n_threads)
+        new, m_new, g_out, norms = compensate_stage_bf16(versions, g0, master, K, lam_used, eta, n_threads)
         out.update(new=new, master=m_new, g=g_out, norms=norms)
     else:
-        new, g_out, norms = compensate_stage_f32(versions, g0, K, lam_new, eta, n_threads)
+        new, g_out, norms = compensate_stage_f32(versions, g0, K, lam_used, eta, n_threads)
         out.update(new=new, g=g_out, norms=norms)
     return out
 

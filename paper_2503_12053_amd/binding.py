@@ -44,7 +44,7 @@ class ferret_tuning(ctypes.Structure):
 
 class ferret_adaptive(ctypes.Structure):
     _fields_ = [("lambda_", c_void_p), ("v_r", c_void_p), ("v_a", c_void_p), ("alpha", c_float),
-                ("eta_lambda", c_float)]
+                ("eta_lambda", c_float), ("fused", c_int32), ("reserved", c_int32)]
 
 
 class ferret_accumulate(ctypes.Structure):
@@ -220,8 +220,8 @@ def ferret_compensate_step(plan: "Plan", ring, grads, master, lam: float, lr: fl
 
 def ferret_compensate_step_adaptive(plan: "Plan", ring, grads, master, lambda_dev, v_r, v_a, alpha: float,
                                     eta_lambda: float, lr: float, norms_out=None, grad_out=None,
-                                    workspace=None, stream=None) -> None:
-    ad = ferret_adaptive(_ptr(lambda_dev), _ptr(v_r), _ptr(v_a), alpha, eta_lambda)
+                                    workspace=None, stream=None, fused: bool = False) -> None:
+    ad = ferret_adaptive(_ptr(lambda_dev), _ptr(v_r), _ptr(v_a), alpha, eta_lambda, int(fused), 0)
     _check(load().ferret_compensate_step_adaptive(plan.handle, _ptr(ring), _ptr(grads), _ptr(master), byref(ad), lr,
                                                   _ptr(norms_out), _ptr(grad_out), _ptr(workspace),
                                                   _stream(stream)))
@@ -431,10 +431,10 @@ class DeviceState:
             self.workspace = torch.zeros(max(self.plan.workspace_bytes // 4, 4), **z)
 
     def step_adaptive(self, alpha: float, eta_lambda: float, lr: float, norms: bool = True, grad_out: bool = True,
-                      stream=None) -> None:
+                      stream=None, fused: bool = False) -> None:
         ferret_compensate_step_adaptive(self.plan, self.ring, self.grads, self.master, self.lambda_dev, self.v_r,
                                         self.v_a, alpha, eta_lambda, lr, self.norms if norms else None,
-                                        self.grad_out if grad_out else None, self.workspace, stream)
+                                        self.grad_out if grad_out else None, self.workspace, stream, fused)
 
     def commit(self, stage: int = -1) -> None:
         ferret_push_version(self.plan, self.ring, None, stage, None)

@@ -225,7 +225,8 @@ size_t ferret_plan_ring_bytes(const ferret_plan *plan) { return plan ? (size_t)(
 size_t ferret_plan_grad_bytes(const ferret_plan *plan) { return plan ? (size_t)(plan->flat_elems * storage_bytes(plan->prec)) : 0; }
 size_t ferret_plan_master_bytes(const ferret_plan *plan) { return plan ? (size_t)(plan->flat_elems * 4) : 0; }
 size_t ferret_plan_workspace_bytes(const ferret_plan *plan) {
-    return plan ? (size_t)round_up(plan->n_chunks * 3 * (int64_t)sizeof(float), 256) : 0;
+    // five per-chunk series: three norms and the two inner products of the lambda block
+    return plan ? (size_t)round_up(plan->n_chunks * 5 * (int64_t)sizeof(float), 256) : 0;
 }
 int64_t ferret_plan_total_params(const ferret_plan *plan) { return plan ? plan->total_params : -1; }
 
@@ -435,6 +436,9 @@ ferret_status ferret_compensate_step_adaptive(const ferret_plan *plan, void *rin
         return FERRET_EINVAL;
     }
     if (plan->n_iters == 0) { set_error("%s: the plan has n_iters = 0, there is nothing for lambda to scale", who); return FERRET_EINVAL; }
+    if ((ad->fused != 0 && ad->fused != 1) || ad->reserved != 0) {
+        set_error("%s: fused = %d (need 0 or 1), reserved = %d (need 0)", who, ad->fused, ad->reserved); return FERRET_EINVAL;
+    }
     StepArgs a;
     fill_step_args(plan, a, ring, grads, master, 0.f, lr, norms_out, grad_out, workspace);
     a.lambda_dev = ad->lambda;
@@ -443,7 +447,10 @@ ferret_status ferret_compensate_step_adaptive(const ferret_plan *plan, void *rin
     a.alpha = ad->alpha;
     a.eta_lambda = ad->eta_lambda;
     int err = 0;
-    if (ad->eta_lambda > 0.f) {
+    if (ad->eta_lambda > 0.f && ad->fused) {
+        a.fused_lambda = 1;                                // one pass: the step kernel runs the lambda block too
+        a.partials = static_cast<float *>(workspace);
+    } else if (ad->eta_lambda > 0.f) {
         float *step_partials = a.partials;
         a.partials = static_cast<float *>(workspace);
         err = launch_lambda_update(*plan, a, hip_stream);

@@ -39,13 +39,13 @@ struct StepArgs {
     const void *grads;
     float *master;
     float *grad_out;   // nullable
-    float *partials;   // float[3][n_chunks] (three series, each contiguous), nullable
+    float *partials;   // float[5][n_chunks] (five series, each contiguous: 3 norms, 2 lambda inner products), nullable
     float lambda;
     float lr;
     uint32_t n_stages;
     uint32_t n_chunks;
     uint32_t chunk_elems;
-    uint32_t pad_;
+    uint32_t fused_lambda;   // 1: the step kernel also runs the "update lambda" block (series 3, 4 of partials)
     // self-tuned lambda (null / zero for the fixed-lambda step)
     float *lambda_dev;   // float[n_stages]; when set, stage j uses lambda_dev[j] instead of `lambda`
     float *v_r;

@@ -141,6 +141,10 @@ using Bf16Store = Bf16Store8;
 using Bf16Store = Bf16Store4;
 #endif
 
+// Per-chunk partial sums a step can produce: series 0..2 are the three norms, series 3..4 the two inner
+// products of the "update lambda" block when that block is fused into the step (OUT & 16).
+constexpr int kSeries = 5;
+
 // A_I applied in place: g <- g + lambda * g * g * (v_new - v_old)
 __device__ __forceinline__ float approximator(float g, float lambda, float v_new, float v_old) {
     return fmaf(lambda * g * g, v_new - v_old, g);
@@ -160,6 +164,9 @@ struct ChunkPtrs {
     float acc_scale;                // factor applied to the sum at the update
     bool acc_update;                // this arrival completes the group: update and clear the sum
     float pen_scale, pen_inv_c;     // step-size penalty of the comparison methods (OUT & 8)
+    const char *v1;                 // V[1], the version one step after V[0] (fused lambda block, OUT & 16)
+    char *v_r, *v_a;                // fp32 moving averages of the lambda block
+    float alpha;
 };
 
 template <typename T>
@@ -251,18 +258,66 @@ __device__ __forceinline__ void update_and_store(const ChunkPtrs<NV> &p, uint32_
     st_off(p.out, vec * (uint32_t)S::kRawBytes, S::narrow(w));
 }
 
+// What the fused lambda block loads per lane-vector besides the step's own inputs.
+template <typename S>
+struct LambdaIn {
+    typename S::Raw v1;
+    v4f vr[S::kF4], va[S::kF4];
+};
+
+template <typename S, int OUT, int NV>
+__device__ __forceinline__ void load_lambda_in(const ChunkPtrs<NV> &p, uint32_t vec, LambdaIn<S> &in) {
+    if (OUT & 16) {
+        in.v1 = ld_off<typename S::Raw>(p.v1, vec * (uint32_t)S::kRawBytes);
+#pragma unroll
+        for (int q = 0; q < S::kF4; ++q) {
+            in.vr[q] = ld_off<v4f>(p.v_r, vec * (uint32_t)(S::kElems * 4) + 16u * q);
+            in.va[q] = ld_off<v4f>(p.v_a, vec * (uint32_t)(S::kElems * 4) + 16u * q);
+        }
+    }
+}
+
+// Alg. 1, block "update lambda", on one lane-vector: its share of <v_a, g_0 - v_r> and <v_a, v_a> on
+// the OLD averages, then v_r <- alpha v_r + (1-alpha) g_0 and v_a <- alpha v_a + (1-alpha) g_0 g_0 (V[1]-V[0]).
+template <typename S, int NV>
+__device__ __forceinline__ void lambda_state_vector(const ChunkPtrs<NV> &p, uint32_t vec, const float (&g)[S::kElems],
+                                                    const float (&w0)[S::kElems], const LambdaIn<S> &in,
+                                                    float (&acc)[kSeries]) {
+    constexpr uint32_t FB = S::kElems * 4;
+    float w1[S::kElems];
+    S::widen(in.v1, w1);
+    const float alpha = p.alpha, beta = 1.0f - p.alpha;
+#pragma unroll
+    for (int q = 0; q < S::kF4; ++q) {
+        float r[4] = {in.vr[q].x, in.vr[q].y, in.vr[q].z, in.vr[q].w};
+        float s4[4] = {in.va[q].x, in.va[q].y, in.va[q].z, in.va[q].w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float gi = g[4 * q + i];
+            acc[3] = fmaf(s4[i], gi - r[i], acc[3]);
+            acc[4] = fmaf(s4[i], s4[i], acc[4]);
+            r[i] = fmaf(alpha, r[i], beta * gi);
+            s4[i] = fmaf(alpha, s4[i], beta * (gi * gi * (w1[4 * q + i] - w0[4 * q + i])));
+        }
+        st_off(p.v_r, vec * FB + 16u * q, make_v4f(r[0], r[1], r[2], r[3]));
+        st_off(p.v_a, vec * FB + 16u * q, make_v4f(s4[0], s4[1], s4[2], s4[3]));
+    }
+}
+
 // Finish one vector: iterate, update, store.  raw_g / raw_v hold the loaded inputs.
 template <typename S, int NV, bool COMP, bool NORMS, int OUT>
 __device__ __forceinline__ void finish_vector(const ChunkPtrs<NV> &p, uint32_t vec,
                                               const typename S::Raw &raw_g,
                                               const typename S::Raw (&raw_v)[NV], const v4f (&m_in)[S::kF4],
-                                              const v4f (&ac_in)[S::kF4], float lambda, float lr, float (&acc)[3]) {
+                                              const v4f (&ac_in)[S::kF4], const LambdaIn<S> &lin, float lambda,
+                                              float lr, float (&acc)[kSeries]) {
     constexpr int E = S::kElems;
     float g[E], prev[E], cur[E], first[E];
     S::widen(raw_g, g);
     S::widen(raw_v[0], prev);
 #pragma unroll
     for (int e = 0; e < E; ++e) first[e] = prev[e];
+    if (OUT & 16) lambda_state_vector<S, NV>(p, vec, g, first, lin, acc);
     if (NORMS) {
 #pragma unroll
         for (int e = 0; e < E; ++e) acc[0] = fmaf(g[e], g[e], acc[0]);
@@ -294,7 +349,7 @@ __device__ __forceinline__ void finish_vector(const ChunkPtrs<NV> &p, uint32_t v
 // each vector is read and written by the same lane.
 template <typename S, int NV, bool COMP, bool NORMS, int OUT>
 __device__ __forceinline__ void run_chunk(const ChunkPtrs<NV> &p, uint32_t n_vecs, float lambda,
-                                          float lr, float (&acc)[3]) {
+                                          float lr, float (&acc)[kSeries]) {
     using Raw = typename S::Raw;
     constexpr uint32_t RB = S::kRawBytes;
     const uint32_t tid = threadIdx.x;
@@ -304,6 +359,7 @@ __device__ __forceinline__ void run_chunk(const ChunkPtrs<NV> &p, uint32_t n_vec
     for (uint32_t base = 0; base < n_grouped; base += group) {
         Raw rg[kUnroll], rv[kUnroll][NV];
         v4f m[kUnroll][S::kF4], ac[kUnroll][S::kF4];
+        LambdaIn<S> lin[kUnroll];
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) rg[u] = ld_off<Raw>(p.g, (base + u * kThreads + tid) * RB);
 #pragma unroll
@@ -314,22 +370,25 @@ __device__ __forceinline__ void run_chunk(const ChunkPtrs<NV> &p, uint32_t n_vec
         for (int u = 0; u < kUnroll; ++u) {
             load_master<S>(p.master, base + u * kThreads + tid, m[u], !(OUT & 2) || p.acc_update);
             load_accum<S, OUT>(p.accum, base + u * kThreads + tid, ac[u]);
+            load_lambda_in<S, OUT>(p, base + u * kThreads + tid, lin[u]);
             if constexpr ((OUT & 4) != 0 && S::kMaster) rv[u][NV - 1] = newest_from_master<S>(m[u]);
         }
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u)
-            finish_vector<S, NV, COMP, NORMS, OUT>(p, base + u * kThreads + tid, rg[u], rv[u], m[u], ac[u], lambda,
-                                                   lr, acc);
+            finish_vector<S, NV, COMP, NORMS, OUT>(p, base + u * kThreads + tid, rg[u], rv[u], m[u], ac[u], lin[u],
+                                                   lambda, lr, acc);
     }
     for (uint32_t vec = n_grouped + tid; vec < n_vecs; vec += kThreads) {
         Raw rg = ld_off<Raw>(p.g, vec * RB), rv[NV];
         v4f m[S::kF4], ac[S::kF4];
+        LambdaIn<S> lin;
 #pragma unroll
         for (int s = 0; s < NV - ((OUT & 4) ? 1 : 0); ++s) rv[s] = ld_off<Raw>(p.v[s], vec * RB);
         load_master<S>(p.master, vec, m, !(OUT & 2) || p.acc_update);
         load_accum<S, OUT>(p.accum, vec, ac);
+        load_lambda_in<S, OUT>(p, vec, lin);
         if constexpr ((OUT & 4) != 0 && S::kMaster) rv[NV - 1] = newest_from_master<S>(m);
-        finish_vector<S, NV, COMP, NORMS, OUT>(p, vec, rg, rv, m, ac, lambda, lr, acc);
+        finish_vector<S, NV, COMP, NORMS, OUT>(p, vec, rg, rv, m, ac, lin, lambda, lr, acc);
     }
 }
 
@@ -338,7 +397,7 @@ __device__ __forceinline__ void run_chunk(const ChunkPtrs<NV> &p, uint32_t n_vec
 template <typename S, bool NORMS, int OUT>
 __device__ __forceinline__ void run_chunk_streamed(const ChunkPtrs<1> &p, const char *arena, uint64_t slot_bytes,
                                                    uint32_t R, uint32_t head, uint32_t tau, uint32_t kp,
-                                                   uint32_t n_vecs, float lambda, float lr, float (&acc)[3]) {
+                                                   uint32_t n_vecs, float lambda, float lr, float (&acc)[kSeries]) {
     using Raw = typename S::Raw;
     constexpr int E = S::kElems;
     constexpr uint32_t RB = S::kRawBytes;
@@ -350,10 +409,13 @@ __device__ __forceinline__ void run_chunk_streamed(const ChunkPtrs<1> &p, const 
         Raw r0 = ld_off<Raw>(arena + (uint64_t)oldest * slot_bytes, vec * RB);      // kp >= 1 here: V[0] is not V[tau]
         load_master<S>(p.master, vec, m, !(OUT & 2) || p.acc_update);
         load_accum<S, OUT>(p.accum, vec, ac);
+        LambdaIn<S> lin;
+        load_lambda_in<S, OUT>(p, vec, lin);
         S::widen(rg, g);
         S::widen(r0, prev);
 #pragma unroll
         for (int e = 0; e < E; ++e) first[e] = prev[e];
+        if (OUT & 16) lambda_state_vector<S, 1>(p, vec, g, first, lin, acc);
         if (NORMS) {
 #pragma unroll
             for (int e = 0; e < E; ++e) acc[0] = fmaf(g[e], g[e], acc[0]);
@@ -435,7 +497,7 @@ __device__ __forceinline__ ChunkInfo chunk_info(const StepArgs &a, const StageDe
 
 // Fixed-NV dispatch target: builds the chunk's pointers.
 template <typename S, int NV, bool COMP, bool NORMS, int OUT>
-__device__ __forceinline__ void do_chunk(const StepArgs &a, const ChunkInfo &c, float lambda, float (&acc)[3]) {
+__device__ __forceinline__ void do_chunk(const StepArgs &a, const ChunkInfo &c, float lambda, float (&acc)[kSeries]) {
     constexpr uint64_t kStoreBytes = S::kStoreBytes;
     ChunkPtrs<NV> p;
     p.g = static_cast<const char *>(a.grads) + c.flat_elem0 * kStoreBytes;
@@ -455,6 +517,10 @@ __device__ __forceinline__ void do_chunk(const StepArgs &a, const ChunkInfo &c, 
     p.acc_update = c.acc_update;
     p.pen_scale = (OUT & 8) ? a.pen_scale[c.stage] : 1.f;
     p.pen_inv_c = (OUT & 8) ? a.pen_inv_c[c.stage] : 0.f;
+    p.v1 = (OUT & 16) ? c.arena + (uint64_t)((oldest + 1) % c.R) * c.slot_bytes : nullptr;
+    p.v_r = (OUT & 16) ? reinterpret_cast<char *>(a.v_r) + c.flat_elem0 * 4 : nullptr;
+    p.v_a = (OUT & 16) ? reinterpret_cast<char *>(a.v_a) + c.flat_elem0 * 4 : nullptr;
+    p.alpha = a.alpha;
     run_chunk<S, NV, COMP, NORMS, OUT>(p, c.n_vecs, lambda, a.lr, acc);
 }
 
@@ -462,8 +528,9 @@ __device__ __forceinline__ void do_chunk(const StepArgs &a, const ChunkInfo &c, 
 // reduces the three partial sums of the workgroup and writes the chunk's partial.
 template <typename S, int LEVEL, bool NORMS, int OUT>
 __device__ __forceinline__ void process_chunk(const StepArgs &a, const ChunkInfo &c, uint32_t chunk,
-                                              float (&red)[3][kWaves]) {
-    float acc[3] = {0.f, 0.f, 0.f};
+                                              float (&red)[kSeries][kWaves]) {
+    float acc[kSeries] = {0.f, 0.f, 0.f, 0.f, 0.f};
+    constexpr int PLAIN = OUT & ~16;      // a stage without staleness has no lambda block
     if (c.skip) {       // uniform: this stage is not part of the call; its norms read as zero
         if (NORMS && threadIdx.x < 3) a.partials[(size_t)threadIdx.x * a.n_chunks + chunk] = 0.f;
         return;
@@ -477,8 +544,8 @@ __device__ __forceinline__ void process_chunk(const StepArgs &a, const ChunkInfo
     // versions to read: the K'+1 boundaries; with K' = 0 only V[tau], plus V[0] when the weight
     // gap is wanted for the norms
     if (c.kp == 0) {
-        if ((NORMS || (OUT & 8)) && c.tau > 0) do_chunk<S, 2, false, NORMS, OUT>(a, c, lambda, acc);
-        else do_chunk<S, 1, false, NORMS, OUT>(a, c, lambda, acc);
+        if ((NORMS || (OUT & 8)) && c.tau > 0) do_chunk<S, 2, false, NORMS, PLAIN>(a, c, lambda, acc);
+        else do_chunk<S, 1, false, NORMS, PLAIN>(a, c, lambda, acc);
     } else if (c.kp == 1) {
         do_chunk<S, 2, true, NORMS, OUT>(a, c, lambda, acc);
     } else if (c.kp == 2) {
@@ -508,22 +575,28 @@ __device__ __forceinline__ void process_chunk(const StepArgs &a, const ChunkInfo
         p.acc_update = c.acc_update;
         p.pen_scale = 1.f;
         p.pen_inv_c = 0.f;
+        p.v1 = (OUT & 16) ? c.arena + (uint64_t)((c.head + c.R - c.tau + 1) % c.R) * c.slot_bytes : nullptr;
+        p.v_r = (OUT & 16) ? reinterpret_cast<char *>(a.v_r) + c.flat_elem0 * 4 : nullptr;
+        p.v_a = (OUT & 16) ? reinterpret_cast<char *>(a.v_a) + c.flat_elem0 * 4 : nullptr;
+        p.alpha = a.alpha;
         run_chunk_streamed<S, NORMS, OUT>(p, c.arena, c.slot_bytes, c.R, c.head, c.tau, c.kp, c.n_vecs,
                                            lambda, a.lr, acc);
     }
-    if (NORMS) {
+    constexpr bool FUSED = (OUT & 16) != 0;
+    if (NORMS || FUSED) {
+        constexpr int k0 = NORMS ? 0 : 3, k1 = FUSED ? kSeries : 3;      // the series this kernel produces
         const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
 #pragma unroll
-        for (int k = 0; k < 3; ++k) {
+        for (int k = k0; k < k1; ++k) {
             float s = wave_sum(acc[k]);
             if (lane == 0) red[k][wave] = s;
         }
         __syncthreads();
-        if (threadIdx.x < 3) {
+        if (threadIdx.x >= (uint32_t)k0 && threadIdx.x < (uint32_t)k1) {
             float s = 0.f;
 #pragma unroll
             for (int w = 0; w < kWaves; ++w) s += red[threadIdx.x][w];
-            a.partials[(size_t)threadIdx.x * a.n_chunks + chunk] = s;     // three series, each contiguous
+            a.partials[(size_t)threadIdx.x * a.n_chunks + chunk] = s;     // each series contiguous
         }
     }
 }
@@ -538,7 +611,7 @@ __device__ __forceinline__ void process_chunk(const StepArgs &a, const ChunkInfo
 //                     need are not compiled in, which keeps the register footprint small.
 template <typename S, bool PERSISTENT, int LEVEL, bool NORMS, int OUT>
 __global__ void __launch_bounds__(kThreads) step_kernel(const StepArgs a) {
-    __shared__ float red[3][kWaves];
+    __shared__ float red[kSeries][kWaves];
     if constexpr (PERSISTENT) {
         __shared__ StageDesc tab[FERRET_MAX_STAGES];
         {   // stage table: kernel-argument segment -> LDS, 12 dwords per stage
@@ -651,10 +724,12 @@ __global__ void __launch_bounds__(kLambdaThreads) lambda_step_kernel(const StepA
     if (a.stage[j].tau == 0) return;
     const uint32_t c0 = a.stage[j].chunk_begin;
     const uint32_t c1 = j + 1 < a.n_stages ? a.stage[j + 1].chunk_begin : a.n_chunks;
+    // the two series: 0 and 1 when the state pass produced them, 3 and 4 when the fused step did
+    const float *dots = a.partials + (size_t)(a.fused_lambda ? 3u : 0u) * a.n_chunks;
     double s0 = 0.0, s1 = 0.0;
     for (uint32_t c = c0 + threadIdx.x; c < c1; c += kLambdaThreads) {
-        s0 += (double)a.partials[c];
-        s1 += (double)a.partials[(size_t)a.n_chunks + c];
+        s0 += (double)dots[c];
+        s1 += (double)dots[(size_t)a.n_chunks + c];
     }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) { s0 += __shfl_xor(s0, off, 64); s1 += __shfl_xor(s1, off, 64); }
@@ -834,13 +909,27 @@ static uint32_t grid_for(const ferret_plan &plan, uint32_t n_chunks, int *err) {
 
 // Resident-workgroup cap.  Measured on MI355X: for steps that stream far more than the 256 MB
 // memory-side cache holds, throughput depends on how many workgroups a CU holds at once, with a sharp
-// optimum that moves with the traffic of one chunk: at the default 2048-element chunks the best count is
-// 6 for K' = 0, 4 for K' = 1, 3 for K' = 2..4, 2 beyond (and 3 for bf16 at K' = 4); one too few costs
-// 5-10 %, one too many 2-5 %.  ceil(120 KiB / bytes one chunk moves) reproduces those counts (K' = 0
-// without norms gets 5 instead of 6).  The launch enforces the count by reserving LDS the kernel never touches: with 160 KiB
-// of LDS per CU, asking for floor(160 KiB / cap) bytes per workgroup lets exactly `cap` of them be resident.
+// optimum that moves with the traffic of one chunk: at the default 2048-element chunks of fp32 the best
+// count is 5 for K' = 0 (4 when the weight gap is read as well), 4 for K' = 1, 3 for K' = 2..4, 2 beyond
+// (and 3 for bf16 at K' = 4); one too few costs 5-10 %, one too many 2-5 %.  ceil(120 KiB / bytes one
+// chunk moves) reproduces those counts.  The launch enforces the count by reserving LDS the kernel never
+// touches: with 160 KiB of LDS per CU, a workgroup that holds floor(160 KiB / cap) bytes lets exactly
+// `cap` of them be resident.
 constexpr uint32_t kLdsPerCu = 160u * 1024u;
 constexpr uint32_t kLdsPerBlockMax = 64u * 1024u;
+// LDS is granted in granules; measured on MI355X: a workgroup asking for 53,744 bytes fits three times
+// into a CU and one asking for 53,776 does not, which is what a 1280-byte granule (160 KiB / 128) gives
+// and a 512- or 1024-byte one would not.  Totals below are multiples of 1280 with every partial granule
+// counted against the workgroup, so they also hold if the granule is 256 or 512 bytes.
+constexpr uint32_t kLdsGranule = 1280u;
+
+// Dynamic LDS bytes that make exactly `cap` workgroups fit a CU, for a kernel with `static_bytes` of its own.
+static uint32_t dyn_lds_for_cap(int32_t cap, uint32_t static_bytes) {
+    if (cap <= 0) return 0;
+    uint32_t total = kLdsPerCu / (uint32_t)cap / kLdsGranule * kLdsGranule;
+    if (total > kLdsPerBlockMax) total = kLdsPerBlockMax;
+    return total > static_bytes ? total - static_bytes : 0u;
+}
 constexpr uint64_t kInFlightTargetBytes = 120u * 1024u;
 constexpr uint64_t kStateTargetBytes = 100u * 1024u;     // the same for lambda_state_kernel
 
@@ -863,9 +952,11 @@ static uint32_t reserve_lds_for_cap(const ferret_plan &plan, const StepArgs &a, 
             const uint32_t versions = kp <= (uint32_t)kUnrolledItersMid ? kp + 1u : 1u + kStreamBatch;
             uint64_t per = sb * (versions + 2u) + (plan.prec == FERRET_F32 ? 0u : 8u);
             if (kp == 0 && a.stage[j].tau > 0 && (a.partials || a.penalized)) per += sb;   // V[0] for the gap
+            if (a.fused_lambda && a.stage[j].tau > 0) per += sb + 8;   // V[1], v_r, v_a
             if (a.accum) per += 8 - sb;     // running sum read + written; most arrivals write no version (measured: 3 at K' = 3)
             per_elem[n] = per;
-            traffic[n] = a.stage[j].n_elems * (sb * (kp + 3u) + (plan.prec == FERRET_F32 ? 0u : 8u));
+            traffic[n] = a.stage[j].n_elems * (sb * (kp + 3u) + (plan.prec == FERRET_F32 ? 0u : 8u) +
+                                               (a.fused_lambda && a.stage[j].tau > 0 ? sb + 16u : 0u));
             total += traffic[n];
             order[n] = n;
             ++n;
@@ -885,12 +976,10 @@ static uint32_t reserve_lds_for_cap(const ferret_plan &plan, const StepArgs &a, 
         if (cap < 2) cap = 2;
         if (cap >= 8) return 0;                               // 8 fit anyway
     }
-    if (cap <= 0) return 0;
-    const uint32_t used = (persistent ? (uint32_t)sizeof(StageDesc) * FERRET_MAX_STAGES : 0u) + 64u;
-    uint32_t want = kLdsPerCu / (uint32_t)cap;
-    want = want / 512u * 512u;                          // LDS is granted in 512-byte granules
-    if (want > kLdsPerBlockMax) want = kLdsPerBlockMax;
-    return want > used + 512u ? want - used - 512u : 0u;
+    // what step_kernel declares itself: the reduction buffer, and the stage table of the persistent variant
+    const uint32_t used = (persistent ? (uint32_t)sizeof(StageDesc) * FERRET_MAX_STAGES : 0u) +
+                          (uint32_t)(kSeries * kWaves * sizeof(float));
+    return dyn_lds_for_cap(cap, used);
 }
 
 template <typename S, bool PERSISTENT, int LEVEL>
@@ -921,6 +1010,26 @@ static hipError_t launch_step_penalized(const StepArgs &a, bool norms, bool gout
     else       { if (gout) FERRET_LAUNCH(false, 9); else FERRET_LAUNCH(false, 8); }
 #undef FERRET_LAUNCH
     return hipGetLastError();
+}
+
+// Launches with the "update lambda" block fused in (one pass; the iterations use lambda as it was before
+// this call's lambda step).
+template <typename S, int LEVEL>
+static hipError_t launch_step_fused_level(const StepArgs &a, bool norms, bool gout, uint32_t grid, uint32_t dyn_lds,
+                                          hipStream_t st) {
+#define FERRET_LAUNCH(NO, OUT) \
+    hipLaunchKernelGGL((step_kernel<S, false, LEVEL, NO, OUT>), dim3(grid), dim3(kThreads), dyn_lds, st, a)
+    if (norms) { if (gout) FERRET_LAUNCH(true, 17); else FERRET_LAUNCH(true, 16); }
+    else       { if (gout) FERRET_LAUNCH(false, 17); else FERRET_LAUNCH(false, 16); }
+#undef FERRET_LAUNCH
+    return hipGetLastError();
+}
+template <typename S>
+static hipError_t launch_step_fused(const StepArgs &a, int level, bool norms, bool gout, uint32_t grid,
+                                    uint32_t dyn_lds, hipStream_t st) {
+    if (level == 0) return launch_step_fused_level<S, 0>(a, norms, gout, grid, dyn_lds, st);
+    if (level == 1) return launch_step_fused_level<S, 1>(a, norms, gout, grid, dyn_lds, st);
+    return launch_step_fused_level<S, 2>(a, norms, gout, grid, dyn_lds, st);
 }
 
 // Gradient-accumulation launches: one workgroup per chunk, every K' covered by one kernel.
@@ -957,10 +1066,13 @@ int launch_step(const ferret_plan &plan, const StepArgs &a, float *norms_out, vo
     const bool norms = norms_out != nullptr, gout = a.grad_out != nullptr;
     const bool timed = g_prof.on && g_prof.used < (int32_t)g_prof.start.size();
     if (timed) (void)hipEventRecord(g_prof.start[g_prof.used], st);
-    const bool persistent = grid < a.n_chunks && !a.accum && !a.penalized;
+    const bool persistent = grid < a.n_chunks && !a.accum && !a.penalized && !a.fused_lambda;
     const uint32_t lds = reserve_lds_for_cap(plan, a, persistent);
     hipError_t e;
-    if (a.penalized)
+    if (a.fused_lambda)
+        e = plan.prec == FERRET_F32 ? launch_step_fused<F32Store>(a, streamed, norms, gout, a.n_chunks, lds, st)
+                                    : launch_step_fused<Bf16Store>(a, streamed, norms, gout, a.n_chunks, lds, st);
+    else if (a.penalized)
         e = plan.prec == FERRET_F32 ? launch_step_penalized<F32Store>(a, norms, gout, a.n_chunks, lds, st)
                                     : launch_step_penalized<Bf16Store>(a, norms, gout, a.n_chunks, lds, st);
     else if (a.accum)
@@ -975,6 +1087,11 @@ int launch_step(const ferret_plan &plan, const StepArgs &a, float *norms_out, vo
                                                              grid, lds, st);
     if (timed) (void)hipEventRecord(g_prof.stop[g_prof.used++], st);
     if (e != hipSuccess) return (int)e;
+    if (a.fused_lambda) {       // lambda takes its step for the next call
+        hipLaunchKernelGGL(lambda_step_kernel, dim3(a.n_stages), dim3(kLambdaThreads), 0, st, a);
+        e = hipGetLastError();
+        if (e != hipSuccess) return (int)e;
+    }
     if (norms) {
         hipLaunchKernelGGL(norms_finalize_kernel, dim3(a.n_stages, 3), dim3(kFinalizeThreads), 0, st, a, norms_out);
         e = hipGetLastError();
@@ -998,9 +1115,7 @@ int launch_lambda_update(const ferret_plan &plan, const StepArgs &a, void *strea
                                             ? (int32_t)((kStateTargetBytes + a.chunk_elems * per - 1) / (a.chunk_elems * per)) : -1);
         if (cap > 0 && cap < 8) {
             if (cap < 2) cap = 2;
-            uint32_t want = kLdsPerCu / (uint32_t)cap / 512u * 512u;
-            if (want > kLdsPerBlockMax) want = kLdsPerBlockMax;
-            lds = want > 1024u ? want - 1024u : 0u;
+            lds = dyn_lds_for_cap(cap, (uint32_t)(2 * kWaves * sizeof(float)));   // the kernel's own red[2][kWaves]
         }
     }
     if (plan.prec == FERRET_F32)

@@ -33,7 +33,7 @@ def _state(w, st, seed, lam0):
     return host
 
 
-def _check(w, plan, st, host, state, lams, alpha, eta_l, K, tag):
+def _check(w, plan, st, host, state, lams, alpha, eta_l, K, tag, fused=False):
     norms = st.norms.cpu().numpy().astype(np.float64)
     lam_gpu = st.lambda_dev.cpu().numpy()
     new_state, new_lams = [], []
@@ -43,7 +43,8 @@ def _check(w, plan, st, host, state, lams, alpha, eta_l, K, tag):
         d = host[j]
         window = d.versions[len(d.versions) - 1 - tau:]
         ref = O.compensate_stage_adaptive(window, d.grads, d.master, K, lams[j], np.float32(alpha), np.float32(eta_l),
-                                          np.float32(w.lr), state[j][0], state[j][1], bf16=bf16)
+                                          np.float32(w.lr), state[j][0], state[j][1], bf16=bf16,
+                                          lambda_step_last=fused)
         t = f"{tag} stage {j}"
         assert lam_gpu[j] == pytest.approx(ref["lam"], rel=1e-5), t + " lambda"
         if tau == 0:
@@ -68,22 +69,53 @@ def _check(w, plan, st, host, state, lams, alpha, eta_l, K, tag):
     return new_state, new_lams
 
 
+@pytest.mark.parametrize("fused", [False, True])
 @pytest.mark.parametrize("precision", ["f32", "bf16"])
 @pytest.mark.parametrize("K", [-1, 2, 1])
-def test_one_adaptive_step(precision, K):
+def test_one_adaptive_step(precision, K, fused):
     w = W.custom_workload("adaptive", [[50_000, 24], [33_001], [20_000], [8_192]], [5, 3, 1, 0], 6, K,
                           precision=precision, seed=31, lam=0.4)
     plan, st, host = PU.load_workload(w, amplified=True)
     state = _state(w, st, 31, w.lam)
     alpha, eta_l = 0.9, 1e-3
-    st.step_adaptive(alpha, eta_l, w.lr)
+    st.step_adaptive(alpha, eta_l, w.lr, fused=fused)
     torch.cuda.synchronize()
-    _, lams = _check(w, plan, st, host, state, [w.lam] * 4, alpha, eta_l, K, f"K={K}")
+    _, lams = _check(w, plan, st, host, state, [w.lam] * 4, alpha, eta_l, K, f"K={K}", fused)
     assert abs(lams[0] - w.lam) > 1e-3           # lambda really moved
     assert lams[3] == np.float32(w.lam)          # the stage without staleness is left alone
 
 
-def test_adaptive_trajectory_over_several_steps():
+@pytest.mark.parametrize("precision", ["f32", "bf16"])
+def test_fused_lambda_block_on_the_streamed_path(precision):
+    """K' beyond the unrolled variants (9 and 12 iterations) and one stage in between, ragged sizes."""
+    w = W.custom_workload("adaptive_deep", [[21_001], [9_000, 40], [5_000]], [12, 9, 6], 13, -1,
+                          precision=precision, seed=35, lam=0.3)
+    plan, st, host = PU.load_workload(w, amplified=True)
+    state = _state(w, st, 35, w.lam)
+    st.step_adaptive(0.8, 1e-3, w.lr, fused=True)
+    torch.cuda.synchronize()
+    _check(w, plan, st, host, state, [w.lam] * 3, 0.8, 1e-3, -1, "deep", True)
+
+
+def test_fused_and_two_pass_agree_on_the_lambda_block():
+    """Both orderings leave the same lambda and averages behind (bit for bit: same per-chunk sums in the same
+    order) when they start from the same state; only the compensated gradient differs."""
+    w = W.custom_workload("adaptive_both", [[30_000], [12_345]], [3, 2], 5, 2, seed=36, lam=0.25)
+    results = []
+    for fused in (False, True):
+        plan, st, host = PU.load_workload(w, amplified=True)
+        _state(w, st, 36, w.lam)
+        st.step_adaptive(0.9, 1e-3, w.lr, fused=fused)
+        torch.cuda.synchronize()
+        results.append((st.lambda_dev.cpu().clone(), st.v_r.cpu().clone(), st.v_a.cpu().clone(),
+                        st.grad_out.cpu().clone()))
+    assert torch.equal(results[0][0], results[1][0])
+    assert torch.equal(results[0][1], results[1][1]) and torch.equal(results[0][2], results[1][2])
+    assert not torch.equal(results[0][3], results[1][3])
+
+
+@pytest.mark.parametrize("fused", [False, True])
+def test_adaptive_trajectory_over_several_steps(fused):
     tau = [2, 1, 0]
     w = W.custom_workload("adaptive_steps", [[30_000], [12_345], [4_096]], tau, 3, -1, seed=32, lam=0.2)
     plan, st, host = PU.load_workload(w, amplified=True)
@@ -96,9 +128,9 @@ def test_adaptive_trajectory_over_several_steps():
             g = W.draw_grads(w, j, w.stage_numel()[j], amplified=True, step=step)
             st.set_flat(st.grads, j, g)
             host[j].grads = g
-        st.step_adaptive(alpha, eta_l, w.lr)
+        st.step_adaptive(alpha, eta_l, w.lr, fused=fused)
         torch.cuda.synchronize()
-        state, lams = _check(w, plan, st, host, state, lams, alpha, eta_l, -1, f"step {step}")
+        state, lams = _check(w, plan, st, host, state, lams, alpha, eta_l, -1, f"step {step}", fused)
         # adopt the device's new version on the host side, then commit
         for j in range(3):
             new = st.get_version(j, plan.stage_write_slot(j))
@@ -125,11 +157,12 @@ def test_zero_eta_lambda_is_the_fixed_lambda_step():
     assert torch.equal(st.lambda_dev.cpu(), torch.full((2,), w.lam))
 
 
-def test_adaptive_step_at_benchmark_shape():
-    """ViT-B-sized workload, the launch configuration bench.py --adaptive times."""
+@pytest.mark.parametrize("fused", [False, True])
+def test_adaptive_step_at_benchmark_shape(fused):
+    """ViT-B-sized workload, the launch configurations bench.py --adaptive / --adaptive-fused time."""
     w = W.make_workload(4)
     plan, st, host = PU.load_workload(w, amplified=True)
     state = _state(w, st, 34, w.lam)
-    st.step_adaptive(0.9, 1e-5, w.lr)
+    st.step_adaptive(0.9, 1e-5, w.lr, fused=fused)
     torch.cuda.synchronize()
-    _check(w, plan, st, host, state, [w.lam] * w.n_stages, 0.9, 1e-5, w.n_iters, "vit")
+    _check(w, plan, st, host, state, [w.lam] * w.n_stages, 0.9, 1e-5, w.n_iters, "vit", fused)

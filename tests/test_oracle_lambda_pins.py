@@ -106,6 +106,44 @@ def test_iterations_use_the_updated_lambda():
     assert out["g"][0] == pytest.approx(2.48, rel=1e-12)
 
 
+def test_one_pass_ordering_uses_the_lambda_it_was_given():
+    """Same hand-worked case with the lambda step applied after the iterations: lambda and the averages come
+    out as before, the compensated gradient is the one of the old lambda."""
+    V = [_f32([1.0]), _f32([1.5])]
+    out = O.compensate_stage_adaptive(V, _f32([2.0]), None, -1, 0.2, 0.5, 0.1, 0.0, _f32([1.0]), _f32([0.5]),
+                                      lambda_step_last=True)
+    ref = O.compensate_stage_adaptive(V, _f32([2.0]), None, -1, 0.2, 0.5, 0.1, 0.0, _f32([1.0]), _f32([0.5]))
+    assert out["lam"] == pytest.approx(0.24, rel=1e-12)
+    assert out["g"][0] == pytest.approx(2.4, rel=1e-7)      # not 2.48
+    assert np.array_equal(out["v_r"], ref["v_r"]) and np.array_equal(out["v_a"], ref["v_a"])
+
+
+def test_one_pass_ordering_is_alg1_shifted_by_one_call():
+    """With the weights held fixed (eta = 0) the lambda block sees the same inputs in either ordering, so the
+    lambda sequences agree and call t of the one-pass ordering compensates with the lambda that Alg. 1's
+    ordering used at call t-1."""
+    rng = np.random.default_rng(11)
+    n = 200
+    V = [(rng.standard_normal(n) * 0.3).astype(np.float32) for _ in range(3)]
+    state = {False: (0.2, np.zeros(n, np.float32), np.zeros(n, np.float32)),
+             True: (0.2, np.zeros(n, np.float32), np.zeros(n, np.float32))}
+    used = {False: [], True: []}
+    for t in range(4):
+        g = rng.standard_normal(n).astype(np.float32)
+        for last in (False, True):
+            lam, vr, va = state[last]
+            out = O.compensate_stage_adaptive(V, g, None, -1, lam, 0.75, 0.05, 0.0, vr, va, lambda_step_last=last)
+            # which lambda scaled this call's iterations: recover it from the first iteration on one element
+            fixed = [O.compensate_stage_f32(V, g, -1, x, 0.0)[1] for x in (lam, out["lam"])]
+            used[last].append(0 if np.array_equal(out["g"], fixed[0]) else 1)
+            assert np.array_equal(out["g"], fixed[used[last][-1]])
+            state[last] = (out["lam"], out["v_r"], out["v_a"])
+        assert state[False][0] == state[True][0]
+        assert np.array_equal(state[False][1], state[True][1]) and np.array_equal(state[False][2], state[True][2])
+    # the first call has zero averages: lambda does not move and both fixed-lambda results coincide
+    assert used[False][1:] == [1, 1, 1] and used[True][1:] == [0, 0, 0]
+
+
 def test_staleness_zero_skips_the_block():
     out = O.compensate_stage_adaptive([_f32([1.0, 2.0])], _f32([1.0, 1.0]), None, -1, 0.2, 0.5, 0.1, 0.5,
                                       _f32([3.0, 3.0]), _f32([4.0, 4.0]))
