@@ -35,7 +35,7 @@ def read_traffic(workload_name: str):
     """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE), if a summary
     for this workload has been committed under profiles/."""
     path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload_name}.txt")
-    if not os.path.exists(path):
+    if workload_name is None or not os.path.exists(path):
         return None
     for line in open(path):
         if line.startswith("traffic_bytes_per_launch:"):
@@ -337,6 +337,14 @@ def main():
     log(f"context: copy kernel {copy_gbs:.0f} GB/s (read+write, {n_copy / 1e6:.0f} MB), "
         f"read-only kernel {read_gbs:.0f} GB/s ({n_read / 1e6:.0f} MB)")
 
+    # the committed counter summaries cover the default step of a workload and its one-pass adaptive variant
+    plain = (not args.accumulate and args.compensator == "iter-fisher" and args.iters is None
+             and not args.newest_from_master and norms)
+    traffic_key = None
+    if plain and not args.adaptive:
+        traffic_key = w.name
+    elif plain and args.adaptive_fused:
+        traffic_key = w.name + "_one_pass_lambda"
     result = {
         "metric": "compensated_params_per_sec",
         "value": params_per_s,
@@ -357,7 +365,7 @@ def main():
                    "algorithmic_bytes_per_step": step_bytes},
         "hbm_gbs_wall": step_bytes / (elapsed / args.steps) / 1e9,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic(w.name),
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic(traffic_key),
                      "kernel": "ferret::step_kernel", "kernel_avg_us": k_avg * 1e3, "kernel_median_us": k_med * 1e3,
                      "copy_kernel_gbs": copy_gbs, "read_kernel_gbs": read_gbs},
     }
