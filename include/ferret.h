@@ -136,7 +136,8 @@ int64_t ferret_plan_ring_elems(const ferret_plan *plan);      /* elements of the
 size_t ferret_plan_ring_bytes(const ferret_plan *plan);
 size_t ferret_plan_grad_bytes(const ferret_plan *plan);       /* storage dtype */
 size_t ferret_plan_master_bytes(const ferret_plan *plan);     /* fp32, flat_elems*4 (also grad_out, src) */
-size_t ferret_plan_workspace_bytes(const ferret_plan *plan);  /* per-chunk partial sums for the norms */
+size_t ferret_plan_workspace_bytes(const ferret_plan *plan);  /* five floats per chunk: partial sums of the
+                                                                  three norms and of the two lambda inner products */
 int64_t ferret_plan_total_params(const ferret_plan *plan);    /* sum of tensor numel (no padding) */
 
 int64_t ferret_plan_stage_params(const ferret_plan *plan, int32_t stage);      /* |w_j|, unpadded */
