@@ -31,7 +31,10 @@ static inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * 
 static inline int64_t vec_elems(ferret_precision p) { return p == FERRET_F32 ? 4 : FERRET_BF16_LANE_ELEMS; }
 static inline int64_t storage_bytes(ferret_precision p) { return p == FERRET_F32 ? 4 : 2; }
 
-constexpr int64_t kThreads = 256;          // workgroup size of every kernel
+#ifndef FERRET_THREADS
+#define FERRET_THREADS 256
+#endif
+constexpr int64_t kThreads = FERRET_THREADS;   // workgroup size of every kernel
 constexpr int64_t kStageAlign = 64;        // stage start alignment in flat buffers / ring
 constexpr int64_t kDefaultSlotAlign = 64;
 
