@@ -283,6 +283,17 @@ ferret_status ferret_accumulate_step(const ferret_plan *plan, void *ring, const 
                                      const ferret_accumulate *accumulate, float lambda, float lr,
                                      float *norms_out, void *grad_out, void *workspace, void *hip_stream);
 
+/* Gradient accumulation with self-tuned lambda: Alg. 1 is run once per arriving gradient, so every
+ * stage that takes part in the call (mode 1 or 2) and whose arrival has staleness >= 1 first runs the
+ * "update lambda" block of ferret_compensate_step_adaptive on this gradient (V[0], V[1] counted from
+ * the version THIS gradient was taken on), then compensates with the new lambda_j and accumulates as
+ * ferret_accumulate_step does.  Stages with mode 0 keep lambda_j, v_r, v_a untouched.
+ * adaptive->fused must be 0 (FERRET_EINVAL otherwise); `workspace` is required. */
+ferret_status ferret_accumulate_step_adaptive(const ferret_plan *plan, void *ring, const void *grads,
+                                              float *master, const ferret_accumulate *accumulate,
+                                              const ferret_adaptive *adaptive, float lr, float *norms_out,
+                                              void *grad_out, void *workspace, void *hip_stream);
+
 /* ---- comparison methods that penalise the step size ------------------------------------------ */
 /* The paper's comparison of compensation methods (Sec. "Comparisons on Gradients Compensation") names
  * "None", "Fisher", "Step-Aware", "Gap-Aware" beside its own.  "None" is n_iters = 0 and "Fisher"

@@ -105,6 +105,8 @@ SIGNATURES = {
     "ferret_compensate_step": (c_int32, [_P, _P, _P, _P, c_float, c_float, _P, _P, _P, _P]),
     "ferret_compensate_step_adaptive": (c_int32, [_P, _P, _P, _P, POINTER(ferret_adaptive), c_float, _P, _P, _P, _P]),
     "ferret_accumulate_step": (c_int32, [_P, _P, _P, _P, POINTER(ferret_accumulate), c_float, c_float, _P, _P, _P, _P]),
+    "ferret_accumulate_step_adaptive": (c_int32, [_P, _P, _P, _P, POINTER(ferret_accumulate), POINTER(ferret_adaptive),
+                                                  c_float, _P, _P, _P, _P]),
     "ferret_pipeline_evaluate": (c_int32, [POINTER(ferret_layer), c_int32, POINTER(c_int32), c_int32, c_int32,
                                            POINTER(c_int32), POINTER(c_int32), POINTER(c_int32), POINTER(c_int32),
                                            ctypes.c_double, ctypes.c_double, POINTER(ctypes.c_double),
@@ -236,6 +238,20 @@ def ferret_accumulate_step(plan: "Plan", ring, grads, master, accum, scale: floa
     acc = ferret_accumulate(_ptr(accum), scale, mode_arr, st_arr)
     _check(load().ferret_accumulate_step(plan.handle, _ptr(ring), _ptr(grads), _ptr(master), byref(acc), lam, lr,
                                          _ptr(norms_out), _ptr(grad_out), _ptr(workspace), _stream(stream)))
+
+
+def ferret_accumulate_step_adaptive(plan: "Plan", ring, grads, master, accum, scale: float, mode: Sequence[int],
+                                    staleness: Optional[Sequence[int]], lambda_dev, v_r, v_a, alpha: float,
+                                    eta_lambda: float, lr: float, norms_out=None, grad_out=None, workspace=None,
+                                    stream=None) -> None:
+    P = plan.n_stages
+    mode_arr = (c_int32 * P)(*[int(m) for m in mode])
+    st_arr = (c_int32 * P)(*[int(x) for x in staleness]) if staleness is not None else None
+    acc = ferret_accumulate(_ptr(accum), scale, mode_arr, st_arr)
+    ad = ferret_adaptive(_ptr(lambda_dev), _ptr(v_r), _ptr(v_a), alpha, eta_lambda, 0, 0)
+    _check(load().ferret_accumulate_step_adaptive(plan.handle, _ptr(ring), _ptr(grads), _ptr(master), byref(acc),
+                                                  byref(ad), lr, _ptr(norms_out), _ptr(grad_out), _ptr(workspace),
+                                                  _stream(stream)))
 
 
 def ferret_penalized_step(plan: "Plan", ring, grads, master, scale: Optional[Sequence[float]],

@@ -420,13 +420,8 @@ ferret_status ferret_compensate_step(const ferret_plan *plan, void *ring, const 
     return FERRET_OK;
 }
 
-ferret_status ferret_compensate_step_adaptive(const ferret_plan *plan, void *ring, const void *grads,
-                                              float *master, const ferret_adaptive *ad, float lr,
-                                              float *norms_out, void *grad_out, void *workspace,
-                                              void *hip_stream) {
-    const char *who = "compensate_step_adaptive";
-    ferret_status rc = check_step_args(who, plan, ring, grads, master, norms_out, grad_out, workspace);
-    if (rc != FERRET_OK) return rc;
+static ferret_status check_adaptive(const char *who, const ferret_plan *plan, const ferret_adaptive *ad,
+                                    void *workspace) {
     if (!ad || !ad->lambda || !ad->v_r || !ad->v_a || !workspace) {
         set_error("%s: null adaptive state (lambda, v_r, v_a) or workspace", who); return FERRET_EINVAL;
     }
@@ -442,13 +437,29 @@ ferret_status ferret_compensate_step_adaptive(const ferret_plan *plan, void *rin
     if ((ad->fused != 0 && ad->fused != 1) || ad->reserved != 0) {
         set_error("%s: fused = %d (need 0 or 1), reserved = %d (need 0)", who, ad->fused, ad->reserved); return FERRET_EINVAL;
     }
-    StepArgs a;
-    fill_step_args(plan, a, ring, grads, master, 0.f, lr, norms_out, grad_out, workspace);
+    return FERRET_OK;
+}
+
+static void set_adaptive_args(StepArgs &a, const ferret_adaptive *ad) {
     a.lambda_dev = ad->lambda;
     a.v_r = ad->v_r;
     a.v_a = ad->v_a;
     a.alpha = ad->alpha;
     a.eta_lambda = ad->eta_lambda;
+}
+
+ferret_status ferret_compensate_step_adaptive(const ferret_plan *plan, void *ring, const void *grads,
+                                              float *master, const ferret_adaptive *ad, float lr,
+                                              float *norms_out, void *grad_out, void *workspace,
+                                              void *hip_stream) {
+    const char *who = "compensate_step_adaptive";
+    ferret_status rc = check_step_args(who, plan, ring, grads, master, norms_out, grad_out, workspace);
+    if (rc != FERRET_OK) return rc;
+    rc = check_adaptive(who, plan, ad, workspace);
+    if (rc != FERRET_OK) return rc;
+    StepArgs a;
+    fill_step_args(plan, a, ring, grads, master, 0.f, lr, norms_out, grad_out, workspace);
+    set_adaptive_args(a, ad);
     int err = 0;
     if (ad->eta_lambda > 0.f && ad->fused) {
         a.fused_lambda = 1;                                // one pass: the step kernel runs the lambda block too
@@ -465,12 +476,17 @@ ferret_status ferret_compensate_step_adaptive(const ferret_plan *plan, void *rin
     return FERRET_OK;
 }
 
-ferret_status ferret_accumulate_step(const ferret_plan *plan, void *ring, const void *grads, float *master,
-                                     const ferret_accumulate *acc, float lambda, float lr, float *norms_out,
-                                     void *grad_out, void *workspace, void *hip_stream) {
-    const char *who = "accumulate_step";
+static ferret_status accumulate_impl(const char *who, const ferret_plan *plan, void *ring, const void *grads,
+                                     float *master, const ferret_accumulate *acc, const ferret_adaptive *ad,
+                                     float lambda, float lr, float *norms_out, void *grad_out, void *workspace,
+                                     void *hip_stream) {
     ferret_status rc = check_step_args(who, plan, ring, grads, master, norms_out, grad_out, workspace);
     if (rc != FERRET_OK) return rc;
+    if (ad) {
+        rc = check_adaptive(who, plan, ad, workspace);
+        if (rc != FERRET_OK) return rc;
+        if (ad->fused) { set_error("%s: the one-pass lambda block is not available with accumulation (fused must be 0)", who); return FERRET_EINVAL; }
+    }
     if (!acc || !acc->accum || !acc->mode) { set_error("%s: null accumulate, accum or mode", who); return FERRET_EINVAL; }
     if (!aligned16(acc->accum)) { set_error("%s: accum must be 16-byte aligned", who); return FERRET_EINVAL; }
     const size_t P = plan->stages.size();
@@ -495,11 +511,37 @@ ferret_status ferret_accumulate_step(const ferret_plan *plan, void *ring, const 
             a.stage[j].kp = (uint16_t)effective_iters(plan->n_iters, tau);
         }
     }
-    int err = launch_step(*plan, a, norms_out, hip_stream);
+    int err = 0;
+    if (ad) {
+        set_adaptive_args(a, ad);
+        if (ad->eta_lambda > 0.f) {      // lambda block of every participating stage, on this arrival's staleness
+            float *step_partials = a.partials;
+            a.partials = static_cast<float *>(workspace);
+            err = launch_lambda_update(*plan, a, hip_stream);
+            a.partials = step_partials;
+        }
+    }
+    if (!err) err = launch_step(*plan, a, norms_out, hip_stream);
     if (err) { set_error("%s: launch failed: %s", who, device_error_string(err)); return FERRET_EDEVICE; }
     for (size_t j = 0; j < P; ++j)
         if (acc->mode[j] == 2) plan->stages[j].step_pending = true;
     return FERRET_OK;
+}
+
+ferret_status ferret_accumulate_step(const ferret_plan *plan, void *ring, const void *grads, float *master,
+                                     const ferret_accumulate *acc, float lambda, float lr, float *norms_out,
+                                     void *grad_out, void *workspace, void *hip_stream) {
+    return accumulate_impl("accumulate_step", plan, ring, grads, master, acc, nullptr, lambda, lr, norms_out,
+                           grad_out, workspace, hip_stream);
+}
+
+ferret_status ferret_accumulate_step_adaptive(const ferret_plan *plan, void *ring, const void *grads,
+                                              float *master, const ferret_accumulate *acc,
+                                              const ferret_adaptive *adaptive, float lr, float *norms_out,
+                                              void *grad_out, void *workspace, void *hip_stream) {
+    if (!adaptive) { set_error("accumulate_step_adaptive: null adaptive"); return FERRET_EINVAL; }
+    return accumulate_impl("accumulate_step_adaptive", plan, ring, grads, master, acc, adaptive, 0.f, lr, norms_out,
+                           grad_out, workspace, hip_stream);
 }
 
 ferret_status ferret_penalized_step(const ferret_plan *plan, void *ring, const void *grads, float *master,

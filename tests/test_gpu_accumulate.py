@@ -117,3 +117,90 @@ def test_skipped_stage_is_left_alone():
     with pytest.raises(B.FerretError) as e:                            # nothing to commit either
         B.ferret_push_version(plan, st.ring, None, 1, None)
     assert e.value.status == B.FERRET_ESTATE
+
+
+@pytest.mark.parametrize("precision", ["f32", "bf16"])
+def test_accumulation_with_self_tuned_lambda(precision):
+    """Per-arrival lambda block + accumulation over several groups: lambda_j, v_r, v_a, the running sum and the
+    versions follow the oracle; a skipped stage keeps its lambda and averages."""
+    ca, tau_max = [2, 3, 1], [2, 1, 0]
+    w = W.custom_workload("accumulate_adaptive", [[25_000, 72], [8_193], [4_096]], tau_max, 3, -1,
+                          precision=precision, seed=54, lam=0.3, lr=0.02)
+    plan, st, host = PU.load_workload(w, amplified=True, ring_depth=B.FERRET_RING_DEPTH_MINIMAL)
+    bf16 = precision == "bf16"
+    st.enable_adaptive(w.lam)
+    accum = torch.zeros(plan.flat_elems, device="cuda")
+    n = w.stage_numel()
+    acc_host = [np.zeros(k, np.float32) for k in n]
+    state = [(np.zeros(k, np.float32), np.zeros(k, np.float32)) for k in n]
+    lams = [np.float32(w.lam)] * 3
+    versions = [list(d.versions) for d in host]
+    master = [None if d.master is None else d.master.numpy().copy() for d in host]
+    alpha, eta_l, scale = 0.75, 2e-3, 0.5
+    count = [0, 0, 0]
+    for m in range(9):
+        mode, stale = [], []
+        for j in range(3):
+            if j == 0 and m == 4:
+                mode.append(0); stale.append(0); continue
+            count[j] += 1
+            mode.append(2 if count[j] % ca[j] == 0 else 1)
+            stale.append((m + j) % (tau_max[j] + 1))
+        for j in range(3):
+            g = W.draw_grads(w, j, n[j], amplified=True, step=m)
+            g = g.to(torch.bfloat16) if bf16 else g
+            st.set_flat(st.grads, j, g)
+            host[j].grads = g
+        write_slots = [plan.stage_write_slot(j) for j in range(3)]
+        B.ferret_accumulate_step_adaptive(plan, st.ring, st.grads, st.master, accum, scale, mode, stale, st.lambda_dev,
+                                          st.v_r, st.v_a, alpha, eta_l, w.lr, st.norms, st.grad_out, st.workspace)
+        torch.cuda.synchronize()
+        lam_gpu = st.lambda_dev.cpu().numpy()
+        for j in range(3):
+            tag = f"micro-step {m} stage {j} mode {mode[j]}"
+            got_r, got_a = st.get_flat(st.v_r, j).numpy(), st.get_flat(st.v_a, j).numpy()
+            if mode[j] == 0:
+                assert lam_gpu[j] == lams[j], tag
+                assert np.array_equal(got_r, state[j][0]) and np.array_equal(got_a, state[j][1]), tag
+                assert np.array_equal(st.get_flat(accum, j).numpy(), acc_host[j]), tag
+                continue
+            tau = min(stale[j], len(versions[j]) - 1)
+            window = versions[j][len(versions[j]) - 1 - tau:]
+            ref = O.accumulate_stage_adaptive(window, host[j].grads, master[j], -1, lams[j], np.float32(alpha),
+                                              np.float32(eta_l), np.float32(w.lr), np.float32(scale), mode[j] == 2,
+                                              acc_host[j], state[j][0], state[j][1], bf16=bf16)
+            assert lam_gpu[j] == pytest.approx(ref["lam"], rel=1e-5), tag + " lambda"
+            if tau == 0:
+                assert lam_gpu[j] == lams[j], tag
+            PU.assert_close_f32(got_r, ref["v_r"], tag + " v_r")
+            PU.assert_close_f32(got_a, ref["v_a"], tag + " v_a")
+            PU.assert_close_f32(st.get_flat(st.grad_out, j).numpy(), ref["g"], tag + " g")
+            got_acc = st.get_flat(accum, j).numpy()
+            PU.assert_close_f32(got_acc, ref["accum"], tag + " accum")
+            acc_host[j], state[j], lams[j] = got_acc.copy(), (got_r.copy(), got_a.copy()), lam_gpu[j]
+            if mode[j] == 2:
+                got_new = st.get_version(j, write_slots[j])
+                if bf16:
+                    got_m = st.get_flat(st.master, j).numpy()
+                    PU.assert_close_f32(got_m, ref["master"], tag + " master")
+                    rms = float(np.sqrt(np.mean(ref["master"].astype(np.float64) ** 2)))
+                    PU.assert_bf16_within_one_ulp(PU.bits_of(got_new), ref["new"], tag + " version",
+                                                  abs_slack=PU.RTOL * rms)
+                    master[j] = got_m.copy()
+                else:
+                    PU.assert_close_f32(got_new.numpy(), ref["new"], tag + " version")
+                versions[j] = (versions[j] + [got_new])[-plan.stage_ring_depth(j):]
+                B.ferret_push_version(plan, st.ring, None, j, None)
+    assert lams[0] != np.float32(w.lam) and lams[2] == np.float32(w.lam)
+
+
+def test_accumulation_with_lambda_rejects_the_one_pass_order():
+    w = W.custom_workload("accumulate_adaptive_bad", [[4_096]], [1], 2, -1, seed=55)
+    plan, st, host = PU.load_workload(w, amplified=True)
+    st.enable_adaptive(w.lam)
+    accum = torch.zeros(plan.flat_elems, device="cuda")
+    acc = B.ferret_accumulate(B._ptr(accum), 1.0, (B.c_int32 * 1)(2), None)
+    ad = B.ferret_adaptive(B._ptr(st.lambda_dev), B._ptr(st.v_r), B._ptr(st.v_a), 0.9, 1e-3, 1, 0)
+    rc = B.load().ferret_accumulate_step_adaptive(plan.handle, B._ptr(st.ring), B._ptr(st.grads), None, B.byref(acc),
+                                                  B.byref(ad), 0.01, None, None, B._ptr(st.workspace), None)
+    assert rc == B.FERRET_EINVAL and "fused" in B.last_error()

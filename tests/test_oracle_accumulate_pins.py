@@ -70,3 +70,34 @@ def test_versions_needed_match_the_papers_count(P, ca):
             version_at_arrival = (m + d) // ca
             worst = max(worst, version_at_arrival - version_at_forward)
         assert worst == math.ceil(d / ca)
+
+
+def test_accumulation_with_lambda_block_hand_worked():
+    """g = 2, V = (1, 1.5), v_r = 1, v_a = .5, alpha = .5, eta_lambda = .1, lambda = .2:
+    dv_r = .5, <v_a,dv_r> = .25, <v_a,v_a> = .25, lambda' = .2 + .2 (.25 - .05) = .24, g_1 = 2 + .24*4*.5 = 2.48;
+    running sum 1 + 2.48 = 3.48; update with scale .5, eta .1: 1.5 - .1*.5*3.48 = 1.326."""
+    f = lambda *x: np.asarray(x, dtype=np.float32)
+    out = O.accumulate_stage_adaptive([f(1.0), f(1.5)], f(2.0), None, -1, 0.2, 0.5, 0.1, 0.1, 0.5, True, f(1.0),
+                                      f(1.0), f(0.5))
+    assert out["lam"] == pytest.approx(0.24, rel=1e-12)
+    assert out["g"][0] == pytest.approx(2.48, rel=1e-7)
+    assert out["new"][0] == np.float32(1.326)
+    assert out["accum"][0] == 0.0
+    assert out["v_r"][0] == np.float32(1.5) and out["v_a"][0] == np.float32(0.25 + 0.5 * 4 * 0.5)
+    # not the last arrival of its group: only the sum moves
+    out = O.accumulate_stage_adaptive([f(1.0), f(1.5)], f(2.0), None, -1, 0.2, 0.5, 0.1, 0.1, 0.5, False, f(1.0),
+                                      f(1.0), f(0.5))
+    assert out["accum"][0] == np.float32(3.48) and "new" not in out
+
+
+def test_accumulation_with_zero_lambda_rate_or_no_staleness_is_plain_accumulation():
+    rng = np.random.default_rng(3)
+    n = 100
+    V = [(rng.standard_normal(n) * 0.2).astype(np.float32) for _ in range(3)]
+    g, acc = rng.standard_normal(n).astype(np.float32), rng.standard_normal(n).astype(np.float32)
+    vr, va = rng.standard_normal(n).astype(np.float32), rng.standard_normal(n).astype(np.float32)
+    a = O.accumulate_stage_adaptive(V, g, None, -1, 0.3, 0.9, 0.0, 0.01, 1.0, True, acc, vr, va)
+    b = O.accumulate_stage(V, g, None, -1, 0.3, 0.01, 1.0, True, acc)
+    assert a["lam"] == 0.3 and np.array_equal(a["new"], b["new"]) and np.array_equal(a["v_r"], vr)
+    a = O.accumulate_stage_adaptive(V[-1:], g, None, -1, 0.3, 0.9, 0.1, 0.01, 1.0, True, acc, vr, va)
+    assert a["lam"] == 0.3 and np.array_equal(a["v_a"], va)
