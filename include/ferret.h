@@ -271,7 +271,10 @@ ferret_status ferret_compensate_step_adaptive(const ferret_plan *plan, void *rin
  *              0 .. tau_j (it varies from arrival to arrival when c^a does not divide P-j-1);
  *              NULL = the plan's tau_j
  * Other arguments as in ferret_compensate_step; norms_out rows of skipped stages read 0.  Commit
- * the stages that were updated with ferret_push_version(.., stage, src = NULL). */
+ * the stages that were updated with ferret_push_version(.., stage, src = NULL).
+ * With a zeroed `accum`, scale 1 and mode 2 for some stages and 0 for the others this is also how to
+ * step a subset of the plan's stages (gradients of different stages arrive at different times in a
+ * pipeline): the result for those stages is bit-identical to ferret_compensate_step. */
 typedef struct {
     float *accum;
     float scale;
