@@ -209,6 +209,14 @@ ferret_status ferret_compensate_step(const ferret_plan *plan, void *ring, const 
                                      float *master, float lambda, float lr, float *norms_out,
                                      void *grad_out, void *workspace, void *hip_stream);
 
+/* The same step for some of the plan's stages only (in a pipeline the gradients of different stages
+ * arrive at different times): stage j takes part iff active[j] != 0 (host int32[n_stages]).  Stages
+ * left out are not read or written, their norms_out rows read 0, and they have nothing to commit.
+ * For the stages that take part the result is bit-identical to ferret_compensate_step. */
+ferret_status ferret_compensate_stages(const ferret_plan *plan, void *ring, const void *grads, float *master,
+                                       const int32_t *active, float lambda, float lr, float *norms_out,
+                                       void *grad_out, void *workspace, void *hip_stream);
+
 /* ---- the step with self-tuned lambda --------------------------------------------------------- */
 /* All of Alg. 1 including its "update lambda" block (Sec. "Iterative Gradient Compensation", Eq.
  * "lambda-objective-v1" and the moving averages after it).  Per stage j with effective staleness
@@ -272,9 +280,7 @@ ferret_status ferret_compensate_step_adaptive(const ferret_plan *plan, void *rin
  *              NULL = the plan's tau_j
  * Other arguments as in ferret_compensate_step; norms_out rows of skipped stages read 0.  Commit
  * the stages that were updated with ferret_push_version(.., stage, src = NULL).
- * With a zeroed `accum`, scale 1 and mode 2 for some stages and 0 for the others this is also how to
- * step a subset of the plan's stages (gradients of different stages arrive at different times in a
- * pipeline): the result for those stages is bit-identical to ferret_compensate_step. */
+ * (To step a subset of stages without accumulation use ferret_compensate_stages.) */
 typedef struct {
     float *accum;
     float scale;

@@ -448,6 +448,25 @@ static void set_adaptive_args(StepArgs &a, const ferret_adaptive *ad) {
     a.eta_lambda = ad->eta_lambda;
 }
 
+ferret_status ferret_compensate_stages(const ferret_plan *plan, void *ring, const void *grads, float *master,
+                                       const int32_t *active, float lambda, float lr, float *norms_out,
+                                       void *grad_out, void *workspace, void *hip_stream) {
+    const char *who = "compensate_stages";
+    ferret_status rc = check_step_args(who, plan, ring, grads, master, norms_out, grad_out, workspace);
+    if (rc != FERRET_OK) return rc;
+    if (!active) { set_error("%s: null active", who); return FERRET_EINVAL; }
+    StepArgs a;
+    fill_step_args(plan, a, ring, grads, master, lambda, lr, norms_out, grad_out, workspace);
+    a.masked = 1;
+    const size_t P = plan->stages.size();
+    for (size_t j = 0; j < P; ++j) a.mode[j] = active[j] ? 2 : 0;
+    int err = launch_step(*plan, a, norms_out, hip_stream);
+    if (err) { set_error("%s: launch failed: %s", who, device_error_string(err)); return FERRET_EDEVICE; }
+    for (size_t j = 0; j < P; ++j)
+        if (active[j]) plan->stages[j].step_pending = true;
+    return FERRET_OK;
+}
+
 ferret_status ferret_compensate_step_adaptive(const ferret_plan *plan, void *ring, const void *grads,
                                               float *master, const ferret_adaptive *ad, float lr,
                                               float *norms_out, void *grad_out, void *workspace,

@@ -56,6 +56,8 @@ struct StepArgs {
     float *accum;        // fp32 flat buffer: running sum of compensated gradients
     float accum_scale;   // factor on the sum at the update
     uint32_t penalized;  // 1: step-size-penalising comparison method (pen_scale / pen_inv_c per stage)
+    uint32_t masked;     // 1: mode[] selects the stages of a plain step (0 skip, 2 step)
+    uint32_t pad_;
     uint8_t mode[FERRET_MAX_STAGES];   // per stage: 0 skip, 1 accumulate only, 2 accumulate + update
     // chunk_begin of every stage again, densely packed (unused entries = UINT32_MAX), so that a
     // workgroup can find its chunk's stage with a few wide scalar loads

@@ -489,7 +489,7 @@ __device__ __forceinline__ ChunkInfo chunk_info(const StepArgs &a, const StageDe
     c.arena = static_cast<const char *>(a.ring) + (uniform(d.ring_base) + e0) * kStoreBytes;
     c.flat_elem0 = uniform(d.flat_off) + e0;
     c.stage = stage;
-    const uint32_t mode = a.accum ? a.mode[stage] : 2u;     // 0 skip, 1 accumulate, 2 accumulate + update
+    const uint32_t mode = (a.accum || a.masked) ? a.mode[stage] : 2u;     // 0 skip, 1 accumulate, 2 (accumulate +) update
     c.acc_update = mode == 2u;
     c.skip = mode == 0u;
     return c;
@@ -946,7 +946,7 @@ static uint32_t reserve_lds_for_cap(const ferret_plan &plan, const StepArgs &a, 
         uint64_t per_elem[FERRET_MAX_STAGES], traffic[FERRET_MAX_STAGES];
         uint32_t order[FERRET_MAX_STAGES], n = 0;
         for (uint32_t j = 0; j < a.n_stages; ++j) {
-            if (a.accum && a.mode[j] == 0) continue;
+            if ((a.accum || a.masked) && a.mode[j] == 0) continue;
             const uint32_t kp = a.stage[j].kp;
             // versions loaded together: all K'+1 on the unrolled paths, V[0] plus a batch on the streamed one
             const uint32_t versions = kp <= (uint32_t)kUnrolledItersMid ? kp + 1u : 1u + kStreamBatch;

@@ -442,3 +442,42 @@ def test_random_configurations(seed):
                           lam=float(rng.choice([0.1, 0.5, -0.3])), lr=float(rng.choice([0.01, 0.2])))
     heads = [int(rng.integers(0, 16)) for _ in range(n_stages)]
     _run(w, True, chunk_elems=chunk, tuning=tuning, ring_depth=depth, n_iters=K, heads=heads)
+
+
+@pytest.mark.parametrize("precision", ["f32", "bf16"])
+@pytest.mark.parametrize("blocks_per_cu", [0, 2])
+def test_stepping_a_subset_of_stages(precision, blocks_per_cu):
+    """Stages that take part get exactly what the full step gives them; the others are left alone and have
+    nothing to commit."""
+    w = W.custom_workload("subset", [[30_000, 8], [12_345], [4_096], [9_000]], [3, 2, 1, 0], 4, 2, precision=precision,
+                          seed=61)
+    tuning = dict(blocks_per_cu=blocks_per_cu) if blocks_per_cu else None
+    plan, st, host = PU.load_workload(w, amplified=True, tuning=tuning)
+    st.step(w.lam, w.lr)
+    torch.cuda.synchronize()
+    full_ring, full_norms, full_g = st.ring.clone(), st.norms.clone(), st.grad_out.clone()
+    full_master = None if st.master is None else st.master.clone()
+    plan2, st2, _ = PU.load_workload(w, amplified=True, tuning=tuning)
+    before_ring = st2.ring.clone()
+    before_master = None if st2.master is None else st2.master.clone()
+    active = [1, 0, 1, 0]
+    B.ferret_compensate_stages(plan2, st2.ring, st2.grads, st2.master, active, w.lam, w.lr, st2.norms, st2.grad_out,
+                               st2.workspace)
+    torch.cuda.synchronize()
+    for j in range(4):
+        lo = plan2.stage_ring_offset(j)
+        hi = lo + plan2.stage_slot_stride(j) * plan2.stage_ring_depth(j)
+        f0, f1 = plan2.stage_flat_offset(j), plan2.stage_flat_offset(j) + plan2.stage_numel(j)
+        want_ring = full_ring if active[j] else before_ring
+        assert torch.equal(st2.ring[lo:hi], want_ring[lo:hi]), f"stage {j} ring"
+        if st2.master is not None:
+            want_m = full_master if active[j] else before_master
+            assert torch.equal(st2.master[f0:f1], want_m[f0:f1]), f"stage {j} master"
+        if active[j]:
+            assert torch.equal(st2.norms[j], full_norms[j]) and torch.equal(st2.grad_out[f0:f1], full_g[f0:f1])
+            B.ferret_push_version(plan2, st2.ring, None, j, None)
+        else:
+            assert not st2.norms[j].any()
+            with pytest.raises(B.FerretError) as e:
+                B.ferret_push_version(plan2, st2.ring, None, j, None)
+            assert e.value.status == B.FERRET_ESTATE
