@@ -68,7 +68,10 @@ ferret_status ferret_pipeline_search(const ferret_layer *layers, int32_t n_layer
                                      int32_t n_stages, double t_d, double memory_budget, double c, double v_d,
                                      ferret_pipeline **out);
 
-/* Alg. 3: partition and configuration with the best rate over all candidate stage-time bounds. */
+/* Alg. 3: partition and configuration with the best rate over all candidate stage-time bounds.
+ * The distinct partitions are searched independently on up to 16 host threads (environment variable
+ * FERRET_PLANNER_THREADS overrides the count); the winner is picked in bound order, so the result does
+ * not depend on the number of threads. */
 ferret_status ferret_pipeline_plan(const ferret_layer *layers, int32_t n_layers, double t_d,
                                    double memory_budget, double c, double v_d, ferret_pipeline **out);
 

@@ -6,10 +6,13 @@
 #pragma STDC FP_CONTRACT OFF   // plain IEEE double operations: decisions between near-equal merits must not
                                // depend on whether the compiler fused a multiply-add
 #include <algorithm>
+#include <atomic>
 #include <cmath>
+#include <cstdlib>
 #include <limits>
 #include <new>
 #include <numeric>
+#include <thread>
 #include <vector>
 
 #include "ferret_internal.h"
@@ -335,7 +338,9 @@ ferret_status ferret_pipeline_plan(const ferret_layer *layers, int32_t n_layers,
 
     ferret_pipeline *best = new (std::nothrow) ferret_pipeline();
     if (!best) { set_error("%s: out of host memory", who); return FERRET_ENOMEM; }
-    std::vector<int32_t> previous_L;      // consecutive bounds often give the same partition: search it once
+    // the distinct partitions, in the order of their bounds (consecutive bounds often give the same one)
+    struct Candidate { std::vector<int32_t> L; double t_c; StageAgg S; SearchResult res; };
+    std::vector<Candidate> cands;
     for (double t_c : bounds) {
         std::vector<int32_t> L{0};
         double t_sum = 0;
@@ -344,14 +349,38 @@ ferret_status ferret_pipeline_plan(const ferret_layer *layers, int32_t n_layers,
             if (t_sum > t_c) { L.push_back(i); t_sum = per[i]; }
         }
         L.push_back(n_layers);
-        if (L == previous_L) continue;      // same partition as the smaller bound before it: same result, and
-        previous_L = L;                     // the comparison below is strict, so the first bound stays recorded
-        StageAgg S;
-        aggregate(layers, n_layers, L.data(), (int)L.size() - 1, S);
-        if ((S.t_f + S.t_b + S.t_f) / t_d > 4096) continue;
-        SearchResult r = search(S, t_d, memory_budget, c, v_d);
-        if (r.rate > best->res.rate) { best->res = std::move(r); best->L = L; best->t_c = t_c; }
+        if (!cands.empty() && L == cands.back().L) continue;      // same partition as the smaller bound before it
+        Candidate cd;
+        aggregate(layers, n_layers, L.data(), (int)L.size() - 1, cd.S);
+        if ((cd.S.t_f + cd.S.t_b + cd.S.t_f) / t_d > 4096) continue;
+        cd.L = std::move(L);
+        cd.t_c = t_c;
+        cands.push_back(std::move(cd));
     }
+    // every partition is searched on its own; the searches share nothing, so they run on several threads and
+    // the winner is then picked in bound order with a strict comparison, exactly as a serial loop would
+    unsigned n_threads = std::thread::hardware_concurrency();
+    if (const char *env = std::getenv("FERRET_PLANNER_THREADS")) n_threads = (unsigned)std::max(1, std::atoi(env));
+    n_threads = std::max(1u, std::min({n_threads, 16u, (unsigned)cands.size()}));
+    std::atomic<size_t> next{0};
+    std::atomic<bool> failed{false};
+    auto work = [&]() {
+        try {
+            for (size_t i = next++; i < cands.size(); i = next++)
+                cands[i].res = search(cands[i].S, t_d, memory_budget, c, v_d);
+        } catch (...) { failed = true; }
+    };
+    {
+        std::vector<std::thread> pool;
+        try {
+            for (unsigned t = 1; t < n_threads; ++t) pool.emplace_back(work);
+        } catch (...) { /* fewer threads than asked for: the calling thread does the rest */ }
+        work();
+        for (std::thread &t : pool) t.join();
+    }
+    if (failed) { delete best; set_error("%s: out of host memory", who); return FERRET_ENOMEM; }
+    for (Candidate &cd : cands)
+        if (cd.res.rate > best->res.rate) { best->res = std::move(cd.res); best->L = std::move(cd.L); best->t_c = cd.t_c; }
     *out = best;
     return FERRET_OK;
 }

@@ -92,6 +92,19 @@ def test_plan_matches_oracle(seed):
     assert got.memory <= M
 
 
+@pytest.mark.parametrize("threads", ["1", "3", "16"])
+def test_plan_does_not_depend_on_the_number_of_search_threads(threads, monkeypatch):
+    rng = random.Random(123)
+    layers = _layers(rng, 14)
+    M = sum(x[2] + x[3] for x in layers) * 2.5
+    monkeypatch.delenv("FERRET_PLANNER_THREADS", raising=False)
+    ref = B.ferret_pipeline_plan(layers, 1.5, M, 0.05, 1.0)
+    monkeypatch.setenv("FERRET_PLANNER_THREADS", threads)
+    got = B.ferret_pipeline_plan(layers, 1.5, M, 0.05, 1.0)
+    assert got.L == ref.L and got.rate == ref.rate and got.memory == ref.memory and got.stage_bound == ref.stage_bound
+    assert got.moves == ref.moves and got.n_workers == ref.n_workers
+
+
 def test_plan_feeds_the_update_path():
     """The planner's per-stage version counts are what ferret_plan_buckets takes as ring depths."""
     layers = [(1.0, 2.0, 4096.0, 100.0)] * 6
