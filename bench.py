@@ -337,9 +337,44 @@ def main():
     log(f"context: copy kernel {copy_gbs:.0f} GB/s (read+write, {n_copy / 1e6:.0f} MB), "
         f"read-only kernel {read_gbs:.0f} GB/s ({n_read / 1e6:.0f} MB)")
 
+    # context: the step's traffic shape without its arithmetic or tables -- per stage, a kernel that adds
+    # NR read streams into one write stream, NR = that stage's read bytes / write bytes, sized so that the
+    # bytes written match the stage's; the time of all stages together against the step's algorithmic bytes
+    mix_gbs = None
+    plain_shape = not args.accumulate and args.compensator == "iter-fisher" and not args.newest_from_master
+    if plain_shape and not args.adaptive:
+        elt = 4 if w.precision == "f32" else 2
+        shapes = []
+        for j in range(w.n_stages):
+            kp = plan.stage_effective_iters(j)
+            rd = elt * (kp + 2) + (0 if w.precision == "f32" else 4)
+            wr = elt + (0 if w.precision == "f32" else 4)
+            nr = max(1, min(8, round(rd / wr)))
+            shapes.append((nr, w.stage_numel()[j] * wr // 16 * 16))
+        need = max((nr + 1) * nb for nr, nb in shapes)
+        if need <= plan.ring_bytes:
+            ring_u8 = st.ring.view(torch.uint8)
+            best = None
+            for cap in (-1, 2, 3, 4, 5):
+                def emulate():
+                    for nr, nb in shapes:
+                        B.ferret_stream_mix(ring_u8[nr * nb:], ring_u8, nb, nr, nb, cap)
+                for _ in range(2):
+                    emulate()
+                ev[0].record()
+                for _ in range(5):
+                    emulate()
+                ev[1].record()
+                torch.cuda.synchronize()
+                t = ev[0].elapsed_time(ev[1]) * 1e-3 / 5
+                best = t if best is None else min(best, t)
+            mix_gbs = plan.step_bytes / best / 1e9
+            log(f"context: same traffic shape without the arithmetic (per stage, {[nr for nr, _ in shapes]} read "
+                f"streams + 1 write stream, best resident cap): {best * 1e6:.1f} us per step-equivalent "
+                f"-> {mix_gbs:.0f} GB/s")
+
     # the committed counter summaries cover the default step of a workload and its one-pass adaptive variant
-    plain = (not args.accumulate and args.compensator == "iter-fisher" and args.iters is None
-             and not args.newest_from_master and norms)
+    plain = plain_shape and args.iters is None and norms
     traffic_key = None
     if plain and not args.adaptive:
         traffic_key = w.name
@@ -367,7 +402,7 @@ def main():
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic(traffic_key),
                      "kernel": "ferret::step_kernel", "kernel_avg_us": k_avg * 1e3, "kernel_median_us": k_med * 1e3,
-                     "copy_kernel_gbs": copy_gbs, "read_kernel_gbs": read_gbs},
+                     "copy_kernel_gbs": copy_gbs, "read_kernel_gbs": read_gbs, "mix_kernel_gbs": mix_gbs},
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, host, plan)

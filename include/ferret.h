@@ -333,6 +333,15 @@ ferret_status ferret_copy_bytes(void *dst, const void *src, size_t n_bytes, void
  * only in the practically impossible case that the data sums to a magic value; it exists so that the
  * loads cannot be optimised away).  The read ceiling of the machine for the same launch shape. */
 ferret_status ferret_read_bytes(const void *src, size_t n_bytes, void *sink, void *hip_stream);
+/* Mixed companion with the traffic shape of the step and none of its arithmetic: n_reads (1..8) streams
+ * of n_bytes each, src_i = src + i * src_stride_bytes, are added element-wise as fp32 and written to dst
+ * (n_bytes; must not overlap any source).  Non-temporal 16-byte accesses, one workgroup per 8 KiB of each
+ * stream, all loads of a vector before its store, exactly like the step.  resident_cap > 0 limits the
+ * workgroups resident per CU the way ferret_tuning.resident_cap does, <= 0 leaves it to the hardware.
+ * n_bytes and src_stride_bytes multiples of 16, 16-byte aligned pointers.  What this kernel reaches for
+ * "K'+2 reads + 1 write" is the ceiling for the step kernel on the machine at hand. */
+ferret_status ferret_stream_mix(void *dst, const void *src, size_t src_stride_bytes, int32_t n_reads,
+                                size_t n_bytes, int32_t resident_cap, void *hip_stream);
 
 /* ---- measurement ------------------------------------------------------------------------------ */
 /* Per-launch timing of the fused step kernel with HIP events recorded on the step's own stream,

@@ -135,6 +135,7 @@ SIGNATURES = {
     "ferret_last_error": (c_char_p, []),
     "ferret_version": (c_char_p, []),
     "ferret_copy_bytes": (c_int32, [_P, _P, c_size_t, _P]),
+    "ferret_stream_mix": (c_int32, [_P, _P, c_size_t, c_int32, c_size_t, c_int32, _P]),
     "ferret_read_bytes": (c_int32, [_P, c_size_t, _P, _P]),
     "ferret_profile_begin": (c_int32, [c_int32]),
     "ferret_profile_end": (c_int32, [POINTER(c_float), c_int32, POINTER(c_int32)]),
@@ -270,6 +271,12 @@ def ferret_penalized_step(plan: "Plan", ring, grads, master, scale: Optional[Seq
     ic = (c_float * P)(*inv_c) if inv_c is not None else None
     _check(load().ferret_penalized_step(plan.handle, _ptr(ring), _ptr(grads), _ptr(master), sc, ic, lr,
                                         _ptr(norms_out), _ptr(grad_out), _ptr(workspace), _stream(stream)))
+
+
+def ferret_stream_mix(dst, src, src_stride_bytes: int, n_reads: int, n_bytes: int, resident_cap: int = 0,
+                      stream=None) -> None:
+    _check(load().ferret_stream_mix(_ptr(dst), _ptr(src), src_stride_bytes, n_reads, n_bytes, resident_cap,
+                                    _stream(stream)))
 
 
 def ferret_copy_bytes(dst, src, n_bytes: int, stream=None) -> None:

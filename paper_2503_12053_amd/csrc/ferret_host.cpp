@@ -611,6 +611,31 @@ ferret_status ferret_read_bytes(const void *src, size_t n_bytes, void *sink, voi
     return FERRET_OK;
 }
 
+ferret_status ferret_stream_mix(void *dst, const void *src, size_t src_stride_bytes, int32_t n_reads,
+                                size_t n_bytes, int32_t resident_cap, void *hip_stream) {
+    if (!dst || !src || !aligned16(dst) || !aligned16(src) || (n_bytes & 15u) || (src_stride_bytes & 15u)) {
+        set_error("stream_mix: need non-null 16-byte aligned pointers, n_bytes and stride multiples of 16");
+        return FERRET_EINVAL;
+    }
+    if (n_reads < 1 || n_reads > 8 || resident_cap > 32) {
+        set_error("stream_mix: n_reads = %d (need 1..8), resident_cap = %d (need <= 32)", n_reads, resident_cap);
+        return FERRET_EINVAL;
+    }
+    if (n_reads > 1 && src_stride_bytes < n_bytes) {
+        set_error("stream_mix: source streams overlap (stride %zu < %zu bytes)", src_stride_bytes, n_bytes);
+        return FERRET_EINVAL;
+    }
+    {   // dst must not overlap the sources
+        const uintptr_t d0 = reinterpret_cast<uintptr_t>(dst), d1 = d0 + n_bytes;
+        const uintptr_t s0 = reinterpret_cast<uintptr_t>(src), s1 = s0 + (size_t)(n_reads - 1) * src_stride_bytes + n_bytes;
+        if (d0 < s1 && s0 < d1) { set_error("stream_mix: dst overlaps the sources"); return FERRET_EINVAL; }
+    }
+    if (n_bytes == 0) return FERRET_OK;
+    int err = launch_mix(dst, src, src_stride_bytes, n_reads, n_bytes, resident_cap, hip_stream);
+    if (err) { set_error("stream_mix: launch failed: %s", device_error_string(err)); return FERRET_EDEVICE; }
+    return FERRET_OK;
+}
+
 ferret_status ferret_profile_begin(int32_t capacity) {
     if (capacity < 1 || capacity > (1 << 20)) { set_error("profile_begin: capacity = %d", capacity); return FERRET_EINVAL; }
     int err = profile_begin(capacity);

@@ -133,6 +133,8 @@ int launch_lambda_update(const ferret_plan &plan, const StepArgs &args, void *st
 int launch_push(const ferret_plan &plan, const PushArgs &args, void *stream);
 int launch_copy(void *dst, const void *src, size_t n_bytes, void *stream);
 int launch_read(const void *src, size_t n_bytes, void *sink, void *stream);
+int launch_mix(void *dst, const void *src, size_t src_stride_bytes, int n_reads, size_t n_bytes, int resident_cap,
+               void *stream);
 const char *device_error_string(int err);
 int profile_begin(int32_t capacity);                       // 0 ok, -1 bad state, >0 hipError_t
 int profile_end(float *ms_out, int32_t cap, int32_t *n_out);

@@ -842,6 +842,28 @@ __global__ void __launch_bounds__(kThreads) read_kernel(const v4u *src, size_t n
     if (s.x == 0x9e3779b9u && s.y == 0x7f4a7c15u && s.z == 0xf39cc060u && s.w == 0x5cedc834u) sink[0] = s;
 }
 
+// Streaming kernel with the step's traffic shape and none of its arithmetic: NR read streams added
+// element-wise into one write stream.  One workgroup per kMixVecsPerLane vectors per lane (8 KiB of each
+// stream), processed one vector at a time: all NR loads, the sum, the store.
+constexpr int kMixVecsPerLane = 2;
+template <int NR>
+__global__ void __launch_bounds__(kThreads) mix_kernel(char *dst, const char *src, size_t stride, size_t n_vecs) {
+    const size_t base = (size_t)blockIdx.x * kThreads * kMixVecsPerLane;
+    const size_t left = n_vecs - base;                                 // > 0 by the launch's grid
+    const uint32_t here = left < (size_t)(kThreads * kMixVecsPerLane) ? (uint32_t)left : (uint32_t)(kThreads * kMixVecsPerLane);
+    const char *s0 = src + base * 16;
+    char *d0 = dst + base * 16;
+    for (uint32_t vec = threadIdx.x; vec < here; vec += kThreads) {
+        v4f x[NR];
+#pragma unroll
+        for (int i = 0; i < NR; ++i) x[i] = ld_off<v4f>(s0 + (size_t)i * stride, vec * 16u);
+        v4f sum = x[0];
+#pragma unroll
+        for (int i = 1; i < NR; ++i) sum += x[i];
+        st_off(d0, vec * 16u, sum);
+    }
+}
+
 // ---- per-launch event timing of the step kernel ---------------------------------------------------
 struct Profiler {
     std::vector<hipEvent_t> start, stop;
@@ -1159,6 +1181,27 @@ int launch_read(const void *src, size_t n_bytes, void *sink, void *stream) {
     if (blocks > 0x7fffffffull) return (int)hipErrorInvalidValue;
     hipLaunchKernelGGL(read_kernel, dim3((uint32_t)blocks), dim3(kThreads), 0, static_cast<hipStream_t>(stream),
                        static_cast<const v4u *>(src), n_vecs, static_cast<v4u *>(sink));
+    return (int)hipGetLastError();
+}
+
+int launch_mix(void *dst, const void *src, size_t src_stride_bytes, int n_reads, size_t n_bytes, int resident_cap,
+               void *stream) {
+    const size_t n_vecs = n_bytes / 16;
+    const size_t per_block = (size_t)kThreads * kMixVecsPerLane;
+    const size_t blocks = (n_vecs + per_block - 1) / per_block;
+    if (blocks > 0x7fffffffull) return (int)hipErrorInvalidValue;
+    const uint32_t lds = dyn_lds_for_cap(resident_cap, 0u);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char *d = static_cast<char *>(dst);
+    const char *s = static_cast<const char *>(src);
+#define FERRET_MIX(NR) \
+    case NR: hipLaunchKernelGGL(mix_kernel<NR>, dim3((uint32_t)blocks), dim3(kThreads), lds, st, d, s, src_stride_bytes, n_vecs); break
+    switch (n_reads) {
+        FERRET_MIX(1); FERRET_MIX(2); FERRET_MIX(3); FERRET_MIX(4);
+        FERRET_MIX(5); FERRET_MIX(6); FERRET_MIX(7); FERRET_MIX(8);
+        default: return (int)hipErrorInvalidValue;
+    }
+#undef FERRET_MIX
     return (int)hipGetLastError();
 }
 

@@ -481,3 +481,31 @@ def test_stepping_a_subset_of_stages(precision, blocks_per_cu):
             with pytest.raises(B.FerretError) as e:
                 B.ferret_push_version(plan2, st2.ring, None, j, None)
             assert e.value.status == B.FERRET_ESTATE
+
+
+@pytest.mark.parametrize("n_reads", [1, 3, 5, 8])
+@pytest.mark.parametrize("cap", [0, 3])
+def test_stream_mix_adds_its_streams(n_reads, cap):
+    n = 3 * 2048 + 1024 + 4                      # whole workgroups, a partial one, a ragged tail
+    stride = n + 12
+    src = torch.randn(n_reads * stride, device="cuda")
+    dst = torch.full((n + 4,), 7.0, device="cuda")
+    B.ferret_stream_mix(dst, src, stride * 4, n_reads, n * 4, cap)
+    torch.cuda.synchronize()
+    want = torch.zeros(n, device="cuda")
+    parts = [src[i * stride:i * stride + n] for i in range(n_reads)]
+    want = parts[0].clone()
+    for p in parts[1:]:
+        want = want + p                           # same left-to-right fp32 order as the kernel
+    assert torch.equal(dst[:n], want) and bool((dst[n:] == 7.0).all())
+
+
+def test_stream_mix_rejects_overlap_and_bad_counts():
+    buf = torch.zeros(4096, device="cuda")
+    for args in [(buf[1024:], buf, 1024 * 4, 2, 1024 * 4 + 16, 0),      # dst overlaps the second source
+                 (buf[2048:], buf, 512 * 4, 2, 1024 * 4, 0),            # sources overlap each other
+                 (buf[2048:], buf, 1024 * 4, 9, 16, 0),
+                 (buf[2048:], buf, 1024 * 4, 0, 16, 0)]:
+        with pytest.raises(B.FerretError) as e:
+            B.ferret_stream_mix(*args)
+        assert e.value.status == B.FERRET_EINVAL
