@@ -509,3 +509,65 @@ def test_stream_mix_rejects_overlap_and_bad_counts():
         with pytest.raises(B.FerretError) as e:
             B.ferret_stream_mix(*args)
         assert e.value.status == B.FERRET_EINVAL
+
+
+@pytest.mark.parametrize("precision", ["f32", "bf16"])
+def test_stage_beyond_four_gibibytes_sampled(precision):
+    """One stage whose fp32 slot-shaped buffers are larger than 4 GiB (element and byte offsets beyond 32 bits
+    inside a stage): the step runs at full size; windows at the start, across the 4 GiB byte boundary and at the
+    ragged end are compared with the oracle element by element (the operation is elementwise, so the oracle of a
+    window is the window of the oracle), and the norms with fp64 reductions over the whole stage."""
+    n_big = (1 << 30) + (1 << 20) + 3 * 2048 + 1024 + 8
+    lam, lr, K = 0.5, 0.01, -1
+    bf16 = precision == "bf16"
+    dt = torch.bfloat16 if bf16 else torch.float32
+    plan = B.ferret_plan_buckets([(10_000, 0), (n_big, 1)], 2, [1, 2], K, 3,
+                                 B.FERRET_BF16_MASTER_F32 if bf16 else B.FERRET_F32, 0)
+    assert plan.stage_numel(1) == n_big and plan.stage_numel(1) * 4 > (1 << 32)
+    gen = torch.Generator(device="cuda").manual_seed(71)
+    ring = torch.empty(plan.ring_elems, device="cuda", dtype=dt).normal_(0.0, 0.05, generator=gen)
+    grads = torch.empty(plan.flat_elems, device="cuda", dtype=dt).normal_(0.0, 1.0, generator=gen)
+    master = torch.empty(plan.flat_elems, device="cuda").normal_(0.0, 0.05, generator=gen) if bf16 else None
+    grad_out = torch.zeros(plan.flat_elems, device="cuda")
+    norms = torch.zeros(2, 3, device="cuda")
+    workspace = torch.zeros(plan.workspace_bytes // 4, device="cuda")
+    plan.set_state([2, 2], [3, 3])
+    assert plan.stage_read_slots(1) == [0, 1, 2] and plan.stage_write_slot(1) == 0
+    off = [plan.slot_offset(1, s) for s in range(3)]
+    f0 = plan.stage_flat_offset(1)
+    W_ = 1 << 19
+    windows = [(0, W_), ((1 << 30) - W_, (1 << 30) + W_), (n_big - W_, n_big)]
+    before = [[ring[off[s] + a: off[s] + b].cpu().clone() for s in range(3)] for a, b in windows]
+    master_before = [master[f0 + a: f0 + b].cpu().clone() for a, b in windows] if bf16 else None
+    # reference sums for the norms, taken before the step overwrites the oldest slot
+    def sq_sum(x):
+        return sum(float((p.double() ** 2).sum()) for p in x.split(1 << 28))
+    want_n0 = sq_sum(grads[f0: f0 + n_big])
+    want_n2 = sum(float(((a.double() - b.double()) ** 2).sum())
+                  for a, b in zip(ring[off[2]: off[2] + n_big].split(1 << 28), ring[off[0]: off[0] + n_big].split(1 << 28)))
+    B.ferret_compensate_step(plan, ring, grads, master, lam, lr, norms, grad_out, workspace)
+    torch.cuda.synchronize()
+    for k, ((a, b), vs) in enumerate(zip(windows, before)):
+        g = grads[f0 + a: f0 + b].cpu()
+        assert g.numel() == b - a and all(v.numel() == b - a for v in vs)
+        tag = f"window [{a}, {b})"
+        got_new = ring[off[0] + a: off[0] + b].cpu()
+        if bf16:
+            new, m_new, g_ref, _ = O.compensate_stage_bf16(vs, g, master_before[k], K, np.float32(lam), np.float32(lr))
+            got_m = master[f0 + a: f0 + b].cpu().numpy()
+            PU.assert_close_f32(got_m, m_new, tag + " master")
+            rms = float(np.sqrt(np.mean(m_new.astype(np.float64) ** 2)))
+            PU.assert_bf16_within_one_ulp(PU.bits_of(got_new), new, tag + " new version", abs_slack=PU.RTOL * rms)
+            PU.assert_bf16_is_rounded_master(PU.bits_of(got_new), got_m, tag)
+        else:
+            new, g_ref, _ = O.compensate_stage_f32(vs, g, K, np.float32(lam), np.float32(lr))
+            PU.assert_close_f32(got_new.numpy(), new, tag + " new version")
+        PU.assert_close_f32(grad_out[f0 + a: f0 + b].cpu().numpy(), g_ref, tag + " g_K'")
+    got = norms.cpu().numpy().astype(np.float64)
+    assert got[1, 0] == pytest.approx(want_n0, rel=PU.RTOL)
+    assert got[1, 2] == pytest.approx(want_n2, rel=PU.RTOL)
+    assert got[1, 1] == pytest.approx(sq_sum(grad_out[f0: f0 + n_big]), rel=PU.RTOL)
+    # the slots that are only read are untouched
+    for s in (1, 2):
+        for (a, b), vs in zip(windows, before):
+            assert torch.equal(ring[off[s] + a: off[s] + b].cpu(), vs[s])
