@@ -274,3 +274,19 @@ def test_accumulate_step_argument_errors(lib):
     assert fn(plan.handle, 16, 16, None, ctypes.byref(bad), 0.5, 0.01, None, None, None, None) == B.FERRET_EINVAL
     assert "staleness" in B.last_error()
     assert ok.scale == 1.0
+
+
+def test_oracle_and_product_do_not_reach_into_each_other():
+    """The oracle is test infrastructure: nothing in the package (sources included) names it, and nothing under
+    oracle/ names the package or its C sources."""
+    pkg = os.path.join(ROOT, "paper_2503_12053_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".cpp", ".hip", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert not re.search(r"^\s*(from|import)\s+oracle\b", text, re.M), f
+                assert "ferret_oracle" not in text and "oracle/" not in text, f
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith((".py", ".c", ".h")):
+            text = open(os.path.join(ROOT, "oracle", f)).read()
+            assert "paper_2503_12053_amd" not in text and "ferret_internal" not in text and "include/ferret" not in text, f
