@@ -298,6 +298,19 @@ def main():
     kernel_ms = B.ferret_profile_end(n_launch) if not args.no_kernel_events else [elapsed * 1e3 / args.steps]
 
     ms_per_step = elapsed * 1e3 / args.steps
+
+    # per-step spread: a second, untimed-for-`value` run of 50 steps with one event between steps
+    # (step period = kernel(s) + launch gaps, as the device sees it)
+    step_med_us = step_min_us = None
+    if not args.graph:
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(51)]
+        marks[0].record()
+        for i in range(50):
+            one_step()
+            marks[i + 1].record()
+        torch.cuda.synchronize()
+        periods = [marks[i].elapsed_time(marks[i + 1]) * 1e3 for i in range(50)]
+        step_med_us, step_min_us = statistics.median(periods), min(periods)
     params_per_s = w.numel / (elapsed / args.steps)
     k_avg = statistics.fmean(kernel_ms)
     k_med = statistics.median(kernel_ms)
@@ -307,6 +320,8 @@ def main():
         elt = 4 if w.precision == "f32" else 2
         per_launch_bytes += sum(elt * n for n, t in zip(w.stage_numel(), w.staleness) if t >= 1)
     achieved = per_launch_bytes / (k_avg * 1e-3) / 1e9     # the fused step kernel alone
+    if step_med_us is not None:
+        log(f"step period on the device over 50 further steps: median {step_med_us:.1f} us, min {step_min_us:.1f} us")
     log(f"step: {ms_per_step * 1e3:.1f} us wall per step; fused kernel avg {k_avg * 1e3:.1f} us, median "
         f"{k_med * 1e3:.1f} us, min {min(kernel_ms) * 1e3:.1f} us -> {achieved:.0f} GB/s algorithmic "
         f"({achieved / HBM_PEAK_GBS:.1%} of {HBM_PEAK_GBS:.0f} GB/s)")
@@ -399,6 +414,7 @@ def main():
                    "chunk_elems": plan.chunk_elems,
                    "algorithmic_bytes_per_step": step_bytes},
         "hbm_gbs_wall": step_bytes / (elapsed / args.steps) / 1e9,
+        "step_median_us": step_med_us, "step_min_us": step_min_us,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic(traffic_key),
                      "kernel": "ferret::step_kernel", "kernel_avg_us": k_avg * 1e3, "kernel_median_us": k_med * 1e3,
