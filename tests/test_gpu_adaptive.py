@@ -166,3 +166,28 @@ def test_adaptive_step_at_benchmark_shape(fused):
     st.step_adaptive(0.9, 1e-5, w.lr, fused=fused)
     torch.cuda.synchronize()
     _check(w, plan, st, host, state, [w.lam] * w.n_stages, 0.9, 1e-5, w.n_iters, "vit", fused)
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_adaptive_configurations(seed):
+    """Random stages, ragged sizes, staleness, ring depth, iteration count, storage type, chunk size, moving-average
+    and lambda rates, either ordering of the lambda block, random head positions."""
+    rng = np.random.default_rng(3000 + seed)
+    n_stages = int(rng.integers(1, 6))
+    R = int(rng.integers(2, 12))
+    tau = [int(rng.integers(0, R)) for _ in range(n_stages)]
+    sizes = [[int(rng.choice([8, 9, 63, 500, 1024, 2047, 2049, 5000, 30_000]) * rng.integers(1, 4))
+              for _ in range(int(rng.integers(1, 4)))] for _ in range(n_stages)]
+    K = int(rng.choice([-1, 1, 2, 3, 5, 9]))
+    precision = "bf16" if seed % 2 else "f32"
+    fused = bool((seed // 2) % 2)
+    chunk = int(rng.choice([0, 1024, 4096]))
+    w = W.custom_workload(f"random_adaptive{seed}", sizes, tau, R, K, precision=precision, seed=4000 + seed,
+                          lam=float(rng.choice([0.1, 0.5, -0.3])), lr=float(rng.choice([0.01, 0.2])))
+    heads = [int(rng.integers(0, 16)) for _ in range(n_stages)]
+    plan, st, host = PU.load_workload(w, amplified=True, chunk_elems=chunk, heads=heads)
+    state = _state(w, st, 4000 + seed, w.lam)
+    alpha, eta_l = float(rng.choice([0.0, 0.5, 0.9])), float(rng.choice([1e-5, 1e-3]))
+    st.step_adaptive(alpha, eta_l, w.lr, fused=fused)
+    torch.cuda.synchronize()
+    _check(w, plan, st, host, state, [w.lam] * n_stages, alpha, eta_l, K, f"seed {seed} fused={fused}", fused)
