@@ -11,6 +11,7 @@ import os
 import shutil
 import subprocess
 import sys
+import tempfile
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
@@ -30,13 +31,32 @@ def hipcc() -> str:
     return exe
 
 
+FLAGS = [f"--offload-arch={ARCH}", "-O3", "-std=c++17", "-fPIC",
+         # keep the compiler from forming packed-fp32 instructions
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-Wall", "-Wno-unused-parameter",
+         "-I", os.path.join(ROOT, "include"), "-I", CSRC]
+
+
 def command(out: str = LIB) -> list:
-    return [hipcc(), f"--offload-arch={ARCH}", "-O3", "-std=c++17", "-fPIC", "-shared",
-            # keep the compiler from forming packed-fp32 instructions
-            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-            "-Wall", "-Wno-unused-parameter",
-            "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-            "-x", "hip", *SOURCES, "-o", out]
+    """The whole library as ONE hipcc command (every source one translation unit each)."""
+    return [hipcc(), *FLAGS, "-shared", "-x", "hip", *SOURCES, "-o", out]
+
+
+def compile_jobs(objdir: str) -> list:
+    """(command, object) per translation unit.  The kernels file is compiled three times with FERRET_TU = 0, 1, 2
+    (small kernels + launch logic / step kernels for fp32 storage / for bf16 storage) so that the parts build
+    in parallel; the two host files are one unit each."""
+    jobs = []
+    kernels = os.path.join(CSRC, "ferret_kernels.hip")
+    for tu in (0, 1, 2):
+        obj = os.path.join(objdir, f"ferret_kernels_tu{tu}.o")
+        jobs.append(([hipcc(), *FLAGS, f"-DFERRET_TU={tu}", "-c", "-x", "hip", kernels, "-o", obj], obj))
+    for src in SOURCES:
+        if src != kernels:
+            obj = os.path.join(objdir, os.path.basename(src) + ".o")
+            jobs.append(([hipcc(), *FLAGS, "-c", "-x", "hip", src, "-o", obj], obj))
+    return jobs
 
 
 def up_to_date() -> bool:
@@ -49,10 +69,20 @@ def up_to_date() -> bool:
 def build(force: bool = False, verbose: bool = True) -> str:
     if not force and up_to_date():
         return LIB
-    cmd = command()
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True)
+    with tempfile.TemporaryDirectory(prefix="ferret_build_") as objdir:
+        jobs = compile_jobs(objdir)
+        procs = []
+        for cmd, _ in jobs:                              # all translation units at once
+            if verbose:
+                print(" ".join(cmd), flush=True)
+            procs.append(subprocess.Popen(cmd))
+        failed = [cmd for (cmd, _), p in zip(jobs, procs) if p.wait() != 0]
+        if failed:
+            raise subprocess.CalledProcessError(1, failed[0])
+        link = [hipcc(), f"--offload-arch={ARCH}", "-shared", "-fPIC", *[obj for _, obj in jobs], "-o", LIB]
+        if verbose:
+            print(" ".join(link), flush=True)
+        subprocess.run(link, check=True)
     return LIB
 
 

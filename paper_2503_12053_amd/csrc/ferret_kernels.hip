@@ -31,6 +31,19 @@
 
 #include "ferret_internal.h"
 
+// The file builds as one translation unit (FERRET_TU undefined) or, to compile in parallel, three times:
+// FERRET_TU = 1 holds the step and state kernels for fp32 storage, 2 those for bf16 storage, 0 everything
+// else (the small kernels, the launch logic, the profiler).
+#ifndef FERRET_TU
+#define FERRET_TU_COMMON 1
+#define FERRET_TU_F32 1
+#define FERRET_TU_BF16 1
+#else
+#define FERRET_TU_COMMON (FERRET_TU == 0)
+#define FERRET_TU_F32 (FERRET_TU == 1)
+#define FERRET_TU_BF16 (FERRET_TU == 2)
+#endif
+
 namespace ferret {
 
 #ifndef FERRET_THREADS
@@ -45,10 +58,10 @@ constexpr int kWaves = kThreads / 64;
 #define FERRET_NT 3                 // bit 0: non-temporal loads, bit 1: non-temporal stores
 #endif
 constexpr int kUnroll = FERRET_UNROLL;   // vectors per lane per stream loaded together when a chunk spans several groups
-constexpr int kUnrolledItersSmall = 4;    // LEVEL 0 kernels: every stage has K' <= 4
-constexpr int kUnrolledItersMid = 8;      // LEVEL 1 kernels: K' <= 8; LEVEL 2 adds the streamed path for any K'
+[[maybe_unused]] constexpr int kUnrolledItersSmall = 4;    // LEVEL 0 kernels: every stage has K' <= 4
+[[maybe_unused]] constexpr int kUnrolledItersMid = 8;      // LEVEL 1 kernels: K' <= 8; LEVEL 2 adds the streamed path for any K'
 constexpr int kStreamBatch = 8;           // boundaries the streamed path loads together
-constexpr uint64_t kCapThresholdBytes = 512ull << 20;
+[[maybe_unused]] constexpr uint64_t kCapThresholdBytes = 512ull << 20;
 
 // 16-byte vectors as clang vector types (so that the non-temporal builtins accept them)
 typedef float v4f __attribute__((ext_vector_type(4)));
@@ -715,6 +728,7 @@ __global__ void __launch_bounds__(kThreads) lambda_state_kernel(const StepArgs a
     }
 }
 
+#if FERRET_TU_COMMON
 // One workgroup per stage: sums the stage's two series in fp64 in a fixed order and takes the
 // gradient-descent step  lambda <- lambda + 2 eta_lambda ((1-alpha) <v_a, g_0 - v_r> - lambda <v_a, v_a>).
 constexpr int kLambdaThreads = 1024;
@@ -1004,6 +1018,8 @@ static uint32_t reserve_lds_for_cap(const ferret_plan &plan, const StepArgs &a, 
     return dyn_lds_for_cap(cap, used);
 }
 
+#endif  // FERRET_TU_COMMON
+
 template <typename S, bool PERSISTENT, int LEVEL>
 static hipError_t launch_step_level(const StepArgs &a, bool norms, bool gout, bool elide, uint32_t grid,
                                     uint32_t dyn_lds, hipStream_t st) {
@@ -1074,6 +1090,41 @@ static hipError_t launch_step_typed(const StepArgs &a, int level, bool norms, bo
     return launch_step_level<S, PERSISTENT, 2>(a, norms, gout, elide, grid, dyn_lds, st);
 }
 
+// What launch_step has decided; the per-type halves below turn it into the kernel launch.
+struct StepLaunch {
+    bool persistent, norms, gout, elide;
+    int level;
+    uint32_t grid, lds;
+};
+
+template <typename S>
+static hipError_t launch_step_for(const StepArgs &a, const StepLaunch &l, hipStream_t st) {
+    if (a.fused_lambda) return launch_step_fused<S>(a, l.level, l.norms, l.gout, a.n_chunks, l.lds, st);
+    if (a.penalized) return launch_step_penalized<S>(a, l.norms, l.gout, a.n_chunks, l.lds, st);
+    if (a.accum) return launch_step_accum<S>(a, l.norms, l.gout, a.n_chunks, l.lds, st);
+    return l.persistent ? launch_step_typed<S, true>(a, l.level, l.norms, l.gout, false, l.grid, l.lds, st)
+                        : launch_step_typed<S, false>(a, l.level, l.norms, l.gout, l.elide, l.grid, l.lds, st);
+}
+template <typename S>
+static hipError_t launch_state_for(const StepArgs &a, uint32_t lds, hipStream_t st) {
+    hipLaunchKernelGGL(lambda_state_kernel<S>, dim3(a.n_chunks), dim3(kThreads), lds, st, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_step_f32(const StepArgs &a, const StepLaunch &l, hipStream_t st);
+hipError_t launch_step_bf16(const StepArgs &a, const StepLaunch &l, hipStream_t st);
+hipError_t launch_state_f32(const StepArgs &a, uint32_t lds, hipStream_t st);
+hipError_t launch_state_bf16(const StepArgs &a, uint32_t lds, hipStream_t st);
+#if FERRET_TU_F32
+hipError_t launch_step_f32(const StepArgs &a, const StepLaunch &l, hipStream_t st) { return launch_step_for<F32Store>(a, l, st); }
+hipError_t launch_state_f32(const StepArgs &a, uint32_t lds, hipStream_t st) { return launch_state_for<F32Store>(a, lds, st); }
+#endif
+#if FERRET_TU_BF16
+hipError_t launch_step_bf16(const StepArgs &a, const StepLaunch &l, hipStream_t st) { return launch_step_for<Bf16Store>(a, l, st); }
+hipError_t launch_state_bf16(const StepArgs &a, uint32_t lds, hipStream_t st) { return launch_state_for<Bf16Store>(a, lds, st); }
+#endif
+
+#if FERRET_TU_COMMON
 int launch_step(const ferret_plan &plan, const StepArgs &a, float *norms_out, void *stream) {
     if (a.n_chunks == 0) return 0;
     int err = 0;
@@ -1088,25 +1139,15 @@ int launch_step(const ferret_plan &plan, const StepArgs &a, float *norms_out, vo
     const bool norms = norms_out != nullptr, gout = a.grad_out != nullptr;
     const bool timed = g_prof.on && g_prof.used < (int32_t)g_prof.start.size();
     if (timed) (void)hipEventRecord(g_prof.start[g_prof.used], st);
-    const bool persistent = grid < a.n_chunks && !a.accum && !a.penalized && !a.fused_lambda;
-    const uint32_t lds = reserve_lds_for_cap(plan, a, persistent);
-    hipError_t e;
-    if (a.fused_lambda)
-        e = plan.prec == FERRET_F32 ? launch_step_fused<F32Store>(a, streamed, norms, gout, a.n_chunks, lds, st)
-                                    : launch_step_fused<Bf16Store>(a, streamed, norms, gout, a.n_chunks, lds, st);
-    else if (a.penalized)
-        e = plan.prec == FERRET_F32 ? launch_step_penalized<F32Store>(a, norms, gout, a.n_chunks, lds, st)
-                                    : launch_step_penalized<Bf16Store>(a, norms, gout, a.n_chunks, lds, st);
-    else if (a.accum)
-        e = plan.prec == FERRET_F32 ? launch_step_accum<F32Store>(a, norms, gout, a.n_chunks, lds, st)
-                                    : launch_step_accum<Bf16Store>(a, norms, gout, a.n_chunks, lds, st);
-    else if (plan.prec == FERRET_F32)
-        e = persistent ? launch_step_typed<F32Store, true>(a, streamed, norms, gout, false, grid, lds, st)
-                       : launch_step_typed<F32Store, false>(a, streamed, norms, gout, false, grid, lds, st);
-    else
-        e = persistent ? launch_step_typed<Bf16Store, true>(a, streamed, norms, gout, false, grid, lds, st)
-                       : launch_step_typed<Bf16Store, false>(a, streamed, norms, gout, plan.newest_from_master != 0,
-                                                             grid, lds, st);
+    StepLaunch l;
+    l.persistent = grid < a.n_chunks && !a.accum && !a.penalized && !a.fused_lambda;
+    l.norms = norms;
+    l.gout = gout;
+    l.elide = plan.newest_from_master != 0;
+    l.level = streamed;
+    l.grid = grid;
+    l.lds = reserve_lds_for_cap(plan, a, l.persistent);
+    hipError_t e = plan.prec == FERRET_F32 ? launch_step_f32(a, l, st) : launch_step_bf16(a, l, st);
     if (timed) (void)hipEventRecord(g_prof.stop[g_prof.used++], st);
     if (e != hipSuccess) return (int)e;
     if (a.fused_lambda) {       // lambda takes its step for the next call
@@ -1141,11 +1182,7 @@ int launch_lambda_update(const ferret_plan &plan, const StepArgs &a, void *strea
             lds = dyn_lds_for_cap(cap, (uint32_t)(2 * kWaves * sizeof(float)));   // the kernel's own red[2][kWaves]
         }
     }
-    if (plan.prec == FERRET_F32)
-        hipLaunchKernelGGL(lambda_state_kernel<F32Store>, dim3(a.n_chunks), dim3(kThreads), lds, st, a);
-    else
-        hipLaunchKernelGGL(lambda_state_kernel<Bf16Store>, dim3(a.n_chunks), dim3(kThreads), lds, st, a);
-    hipError_t e = hipGetLastError();
+    hipError_t e = plan.prec == FERRET_F32 ? launch_state_f32(a, lds, st) : launch_state_bf16(a, lds, st);
     if (e != hipSuccess) return (int)e;
     hipLaunchKernelGGL(lambda_step_kernel, dim3(a.n_stages), dim3(kLambdaThreads), 0, st, a);
     return (int)hipGetLastError();
@@ -1206,5 +1243,6 @@ int launch_mix(void *dst, const void *src, size_t src_stride_bytes, int n_reads,
 }
 
 const char *device_error_string(int err) { return hipGetErrorString(static_cast<hipError_t>(err)); }
+#endif  // FERRET_TU_COMMON
 
 }  // namespace ferret
