@@ -401,9 +401,23 @@ static void fill_step_args(const ferret_plan *plan, StepArgs &a, void *ring, con
     a.n_stages = (uint32_t)plan->stages.size();
     a.n_chunks = (uint32_t)plan->n_chunks;
     a.chunk_elems = (uint32_t)plan->chunk_elems;
+    a.chunk_base = 0;
+    a.chunk_end = a.n_chunks;
     fill_step_descs(*plan, a.stage);
     for (uint32_t j = 0; j < FERRET_MAX_STAGES; ++j)
         a.chunk_begin[j] = j < a.n_stages ? a.stage[j].chunk_begin : UINT32_MAX;
+}
+
+// When mode[] leaves stages out, the launch only has to cover the chunks from the first to the last stage that
+// takes part (stages left out in between still get workgroups, which return at once).
+static void narrow_chunk_span(const ferret_plan *plan, StepArgs &a) {
+    const size_t P = plan->stages.size();
+    size_t first = P, last = 0;
+    for (size_t j = 0; j < P; ++j)
+        if (a.mode[j] != 0) { if (first == P) first = j; last = j; }
+    if (first == P) { a.chunk_base = a.chunk_end = 0; return; }
+    a.chunk_base = (uint32_t)plan->stages[first].chunk_begin;
+    a.chunk_end = (uint32_t)(plan->stages[last].chunk_begin + plan->stages[last].n_chunks);
 }
 
 ferret_status ferret_compensate_step(const ferret_plan *plan, void *ring, const void *grads, float *master,
@@ -460,6 +474,7 @@ ferret_status ferret_compensate_stages(const ferret_plan *plan, void *ring, cons
     a.masked = 1;
     const size_t P = plan->stages.size();
     for (size_t j = 0; j < P; ++j) a.mode[j] = active[j] ? 2 : 0;
+    narrow_chunk_span(plan, a);
     int err = launch_step(*plan, a, norms_out, hip_stream);
     if (err) { set_error("%s: launch failed: %s", who, device_error_string(err)); return FERRET_EDEVICE; }
     for (size_t j = 0; j < P; ++j)
@@ -530,6 +545,7 @@ static ferret_status accumulate_impl(const char *who, const ferret_plan *plan, v
             a.stage[j].kp = (uint16_t)effective_iters(plan->n_iters, tau);
         }
     }
+    narrow_chunk_span(plan, a);
     int err = 0;
     if (ad) {
         set_adaptive_args(a, ad);

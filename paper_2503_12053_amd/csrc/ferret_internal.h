@@ -57,6 +57,8 @@ struct StepArgs {
     float accum_scale;   // factor on the sum at the update
     uint32_t penalized;  // 1: step-size-penalising comparison method (pen_scale / pen_inv_c per stage)
     uint32_t masked;     // 1: mode[] selects the stages of a plain step (0 skip, 2 step)
+    uint32_t chunk_base; // the launch covers chunks [chunk_base, chunk_end): all of them, or the span of the
+    uint32_t chunk_end;  // stages that take part when some are left out
     uint32_t pad_;
     uint8_t mode[FERRET_MAX_STAGES];   // per stage: 0 skip, 1 accumulate only, 2 accumulate + update
     // chunk_begin of every stage again, densely packed (unused entries = UINT32_MAX), so that a

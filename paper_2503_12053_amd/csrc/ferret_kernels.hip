@@ -635,7 +635,7 @@ __global__ void __launch_bounds__(kThreads) step_kernel(const StepArgs a) {
         }
         __syncthreads();
         uint32_t stage = 0;
-        for (uint32_t chunk = blockIdx.x; chunk < a.n_chunks; chunk += gridDim.x) {
+        for (uint32_t chunk = a.chunk_base + blockIdx.x; chunk < a.chunk_end; chunk += gridDim.x) {
             while (stage + 1 < a.n_stages && chunk >= tab[stage + 1].chunk_begin) ++stage;
             stage = uniform(stage);
             const ChunkInfo c = chunk_info<S>(a, tab[stage], chunk, stage);
@@ -643,7 +643,7 @@ __global__ void __launch_bounds__(kThreads) step_kernel(const StepArgs a) {
             if (NORMS) __syncthreads();     // red[] is reused by the next chunk
         }
     } else {
-        const uint32_t chunk = blockIdx.x;
+        const uint32_t chunk = a.chunk_base + blockIdx.x;
         // stage = number of stages (beyond the first) that begin at or before this chunk;
         // unused table entries hold UINT32_MAX and never count
         uint32_t stage = 0;
@@ -669,7 +669,7 @@ __global__ void __launch_bounds__(kThreads) lambda_state_kernel(const StepArgs a
     constexpr int E = S::kElems;
     constexpr uint32_t RB = S::kRawBytes, FB = E * 4;
     __shared__ float red[2][kWaves];
-    const uint32_t chunk = blockIdx.x;
+    const uint32_t chunk = a.chunk_base + blockIdx.x;
     uint32_t stage = 0;
 #pragma unroll
     for (uint32_t j = 1; j < 16; ++j) stage += chunk >= a.chunk_begin[j] ? 1u : 0u;
@@ -766,6 +766,10 @@ constexpr int kFinalizeThreads = 1024;
 __global__ void __launch_bounds__(kFinalizeThreads) norms_finalize_kernel(const StepArgs a, float *norms_out) {
     __shared__ double red[kFinalizeThreads / 64];
     const uint32_t j = blockIdx.x, k = blockIdx.y;
+    if ((a.accum || a.masked) && a.mode[j] == 0) {       // the stage took no part: no partials were written for it
+        if (threadIdx.x == 0) norms_out[j * 3 + k] = 0.f;
+        return;
+    }
     const uint32_t c0 = a.stage[j].chunk_begin;
     const uint32_t c1 = j + 1 < a.n_stages ? a.stage[j + 1].chunk_begin : a.n_chunks;
     const float *series = a.partials + (size_t)k * a.n_chunks;
@@ -1094,20 +1098,21 @@ static hipError_t launch_step_typed(const StepArgs &a, int level, bool norms, bo
 struct StepLaunch {
     bool persistent, norms, gout, elide;
     int level;
+    uint32_t chunks;     // chunks the launch covers (one workgroup each unless persistent)
     uint32_t grid, lds;
 };
 
 template <typename S>
 static hipError_t launch_step_for(const StepArgs &a, const StepLaunch &l, hipStream_t st) {
-    if (a.fused_lambda) return launch_step_fused<S>(a, l.level, l.norms, l.gout, a.n_chunks, l.lds, st);
-    if (a.penalized) return launch_step_penalized<S>(a, l.norms, l.gout, a.n_chunks, l.lds, st);
-    if (a.accum) return launch_step_accum<S>(a, l.norms, l.gout, a.n_chunks, l.lds, st);
+    if (a.fused_lambda) return launch_step_fused<S>(a, l.level, l.norms, l.gout, l.chunks, l.lds, st);
+    if (a.penalized) return launch_step_penalized<S>(a, l.norms, l.gout, l.chunks, l.lds, st);
+    if (a.accum) return launch_step_accum<S>(a, l.norms, l.gout, l.chunks, l.lds, st);
     return l.persistent ? launch_step_typed<S, true>(a, l.level, l.norms, l.gout, false, l.grid, l.lds, st)
                         : launch_step_typed<S, false>(a, l.level, l.norms, l.gout, l.elide, l.grid, l.lds, st);
 }
 template <typename S>
 static hipError_t launch_state_for(const StepArgs &a, uint32_t lds, hipStream_t st) {
-    hipLaunchKernelGGL(lambda_state_kernel<S>, dim3(a.n_chunks), dim3(kThreads), lds, st, a);
+    hipLaunchKernelGGL(lambda_state_kernel<S>, dim3(a.chunk_end - a.chunk_base), dim3(kThreads), lds, st, a);
     return hipGetLastError();
 }
 
@@ -1128,7 +1133,8 @@ hipError_t launch_state_bf16(const StepArgs &a, uint32_t lds, hipStream_t st) { 
 int launch_step(const ferret_plan &plan, const StepArgs &a, float *norms_out, void *stream) {
     if (a.n_chunks == 0) return 0;
     int err = 0;
-    const uint32_t grid = grid_for(plan, a.n_chunks, &err);
+    const uint32_t n_launch = a.chunk_end - a.chunk_base;     // 0: no stage takes part, only the norms are cleared
+    const uint32_t grid = grid_for(plan, n_launch, &err);
     if (err) return err;
     hipStream_t st = static_cast<hipStream_t>(stream);
     int streamed = 0;    // kernel level: which K' the launch has to cover
@@ -1140,14 +1146,16 @@ int launch_step(const ferret_plan &plan, const StepArgs &a, float *norms_out, vo
     const bool timed = g_prof.on && g_prof.used < (int32_t)g_prof.start.size();
     if (timed) (void)hipEventRecord(g_prof.start[g_prof.used], st);
     StepLaunch l;
-    l.persistent = grid < a.n_chunks && !a.accum && !a.penalized && !a.fused_lambda;
+    l.persistent = grid < n_launch && !a.accum && !a.penalized && !a.fused_lambda;
+    l.chunks = n_launch;
     l.norms = norms;
     l.gout = gout;
     l.elide = plan.newest_from_master != 0;
     l.level = streamed;
     l.grid = grid;
     l.lds = reserve_lds_for_cap(plan, a, l.persistent);
-    hipError_t e = plan.prec == FERRET_F32 ? launch_step_f32(a, l, st) : launch_step_bf16(a, l, st);
+    hipError_t e = hipSuccess;
+    if (n_launch > 0) e = plan.prec == FERRET_F32 ? launch_step_f32(a, l, st) : launch_step_bf16(a, l, st);
     if (timed) (void)hipEventRecord(g_prof.stop[g_prof.used++], st);
     if (e != hipSuccess) return (int)e;
     if (a.fused_lambda) {       // lambda takes its step for the next call
@@ -1163,7 +1171,7 @@ int launch_step(const ferret_plan &plan, const StepArgs &a, float *norms_out, vo
 }
 
 int launch_lambda_update(const ferret_plan &plan, const StepArgs &a, void *stream) {
-    if (a.n_chunks == 0) return 0;
+    if (a.n_chunks == 0 || a.chunk_end == a.chunk_base) return 0;
     hipStream_t st = static_cast<hipStream_t>(stream);
     // same kind of resident-workgroup rule as the step (measured optimum for this pass: 2 workgroups per
     // CU at fp32, 352 us against 381 us uncapped at the ViT-B-sized workload); it moves 3 storage elements +

@@ -446,9 +446,10 @@ def test_random_configurations(seed):
     _run(w, True, chunk_elems=chunk, tuning=tuning, ring_depth=depth, n_iters=K, heads=heads)
 
 
+@pytest.mark.parametrize("active", [[1, 0, 1, 0], [0, 0, 0, 1], [0, 1, 1, 0], [0, 0, 0, 0], [1, 1, 1, 1]])
 @pytest.mark.parametrize("precision", ["f32", "bf16"])
 @pytest.mark.parametrize("blocks_per_cu", [0, 2])
-def test_stepping_a_subset_of_stages(precision, blocks_per_cu):
+def test_stepping_a_subset_of_stages(precision, blocks_per_cu, active):
     """Stages that take part get exactly what the full step gives them; the others are left alone and have
     nothing to commit."""
     w = W.custom_workload("subset", [[30_000, 8], [12_345], [4_096], [9_000]], [3, 2, 1, 0], 4, 2, precision=precision,
@@ -462,7 +463,7 @@ def test_stepping_a_subset_of_stages(precision, blocks_per_cu):
     plan2, st2, _ = PU.load_workload(w, amplified=True, tuning=tuning)
     before_ring = st2.ring.clone()
     before_master = None if st2.master is None else st2.master.clone()
-    active = [1, 0, 1, 0]
+    st2.norms.fill_(5.0)
     B.ferret_compensate_stages(plan2, st2.ring, st2.grads, st2.master, active, w.lam, w.lr, st2.norms, st2.grad_out,
                                st2.workspace)
     torch.cuda.synchronize()
