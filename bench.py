@@ -77,9 +77,10 @@ def cpu_baseline(w, host, plan, budget_s=20.0):
         acc += w.stage_numel()[j]
     reps = max(1, min(5, int(budget_s * 0.4 / max(acc / rate1, 1e-3))))
     t1, n1 = min(one_step(1, stages) for _ in range(reps))
-    tn, nn = min(one_step(cores, stages) for _ in range(reps))
+    reps_n = max(reps, min(30, int(budget_s * 0.1 / max(t1 / cores, 1e-3))))     # the threaded runs are short: more of them
+    tn, nn = min(one_step(cores, stages) for _ in range(reps_n))
     sample = (f"one step of stages {stages[0]}..{stages[-1]} of {w.name} ({n1} of {w.numel} parameters), "
-              f"fp64 oracle, best of {reps}: 1 thread {t1:.2f} s, {cores} threads {tn:.2f} s")
+              f"fp64 oracle: 1 thread best of {reps} {t1:.2f} s, {cores} threads best of {reps_n} {tn:.3f} s")
     return {"value": nn / tn, "unit": "params/s", "cores": cores, "kind": "oracle", "sample": sample,
             "single_thread_value": n1 / t1}
 
