@@ -142,6 +142,8 @@ def main():
     ap.add_argument("--slot-align", type=int, default=0)
     ap.add_argument("--slot-skew", type=int, default=0)
     ap.add_argument("--iters", type=int, default=None, help="override K (-1 = one iteration per version step)")
+    ap.add_argument("--precision", choices=["f32", "bf16"], default=None,
+                    help="override the workload's storage type (for sweeps; not a benchmark configuration)")
     ap.add_argument("--adaptive", action="store_true",
                     help="time the self-tuned-lambda step (all of Alg. 1) instead of the fixed-lambda step")
     ap.add_argument("--adaptive-fused", action="store_true",
@@ -178,6 +180,9 @@ def main():
     torch.cuda.set_device(dev)
 
     w = W.make_workload(args.config)
+    if args.precision:                       # sweeps only: the same shapes in the other storage type
+        w.precision = args.precision
+        w.name += "_as_" + args.precision
     if args.iters is not None:
         w.n_iters = args.iters
     if args.compensator in ("none", "step-aware", "gap-aware"):

@@ -433,9 +433,10 @@ __device__ __forceinline__ void run_chunk_streamed(const ChunkPtrs<1> &p, const 
 #pragma unroll
             for (int e = 0; e < E; ++e) acc[0] = fmaf(g[e], g[e], acc[0]);
         }
-        for (uint32_t i = 1; i <= kp; i += kStreamBatch) {     // a batch of boundaries at a time: their loads overlap
+        // Batches of kStreamBatch boundaries, two register sets used in turn: the loads of the next batch are
+        // issued before the iterations of the current one, so memory latency overlaps across batches.
+        auto load_batch = [&](uint32_t i, Raw (&r)[kStreamBatch]) {
             const uint32_t count = kp - i + 1 < (uint32_t)kStreamBatch ? kp - i + 1 : (uint32_t)kStreamBatch;   // uniform
-            Raw r[kStreamBatch];
 #pragma unroll
             for (int b = 0; b < kStreamBatch; ++b) {
                 if ((uint32_t)b >= count) break;
@@ -443,6 +444,9 @@ __device__ __forceinline__ void run_chunk_streamed(const ChunkPtrs<1> &p, const 
                 if ((OUT & 4) != 0 && S::kMaster && i + b == kp) r[b] = newest_from_master<S>(m);
                 else r[b] = ld_off<Raw>(arena + (uint64_t)((oldest + s_i) % R) * slot_bytes, vec * RB);
             }
+        };
+        auto iterate_batch = [&](uint32_t i, const Raw (&r)[kStreamBatch]) {
+            const uint32_t count = kp - i + 1 < (uint32_t)kStreamBatch ? kp - i + 1 : (uint32_t)kStreamBatch;
 #pragma unroll
             for (int b = 0; b < kStreamBatch; ++b) {
                 if ((uint32_t)b >= count) break;
@@ -452,6 +456,17 @@ __device__ __forceinline__ void run_chunk_streamed(const ChunkPtrs<1> &p, const 
                     g[e] = approximator(g[e], lambda, cur[e], prev[e]);
                     prev[e] = cur[e];
                 }
+            }
+        };
+        Raw ra[kStreamBatch], rb[kStreamBatch];
+        load_batch(1, ra);
+        for (uint32_t i = 1; i <= kp; i += 2 * kStreamBatch) {
+            const bool second = i + kStreamBatch <= kp;             // uniform
+            if (second) load_batch(i + kStreamBatch, rb);
+            iterate_batch(i, ra);
+            if (second) {
+                if (i + 2 * kStreamBatch <= kp) load_batch(i + 2 * kStreamBatch, ra);
+                iterate_batch(i + kStreamBatch, rb);
             }
         }
         if (NORMS) {
@@ -988,8 +1003,9 @@ static uint32_t reserve_lds_for_cap(const ferret_plan &plan, const StepArgs &a, 
         for (uint32_t j = 0; j < a.n_stages; ++j) {
             if ((a.accum || a.masked) && a.mode[j] == 0) continue;
             const uint32_t kp = a.stage[j].kp;
-            // versions loaded together: all K'+1 on the unrolled paths, V[0] plus a batch on the streamed one
-            const uint32_t versions = kp <= (uint32_t)kUnrolledItersMid ? kp + 1u : 1u + kStreamBatch;
+            // versions loaded together: all K'+1 on the unrolled paths; on the streamed one a batch counts (measured
+            // with its two register sets used in turn: best cap 3-4 for bf16, 2-3 for fp32, which this reproduces)
+            const uint32_t versions = kp <= (uint32_t)kUnrolledItersMid ? kp + 1u : (uint32_t)kStreamBatch;
             uint64_t per = sb * (versions + 2u) + (plan.prec == FERRET_F32 ? 0u : 8u);
             if (kp == 0 && a.stage[j].tau > 0 && (a.partials || a.penalized)) per += sb;   // V[0] for the gap
             if (a.fused_lambda && a.stage[j].tau > 0) per += sb + 8;   // V[1], v_r, v_a
