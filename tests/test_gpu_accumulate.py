@@ -204,3 +204,31 @@ def test_accumulation_with_lambda_rejects_the_one_pass_order():
     rc = B.load().ferret_accumulate_step_adaptive(plan.handle, B._ptr(st.ring), B._ptr(st.grads), None, B.byref(acc),
                                                   B.byref(ad), 0.01, None, None, B._ptr(st.workspace), None)
     assert rc == B.FERRET_EINVAL and "fused" in B.last_error()
+
+
+def test_accumulation_at_benchmark_shape():
+    """ViT-B-sized workload, the launch configuration bench.py --accumulate 2 times: two arrivals per stage, the
+    second one updates."""
+    w = W.make_workload(4)
+    plan, st, host = PU.load_workload(w, amplified=True)
+    accum = torch.zeros(plan.flat_elems, device="cuda")
+    acc_host = [np.zeros(n, np.float32) for n in w.stage_numel()]
+    for k in range(2):
+        last = k == 1
+        for j in range(w.n_stages):
+            g = W.draw_grads(w, j, w.stage_numel()[j], amplified=True, step=k)
+            st.set_flat(st.grads, j, g)
+            host[j].grads = g
+        _accum_call(plan, st, accum, 0.5, [2 if last else 1] * w.n_stages, None, w.lam, w.lr)
+        for j in range(w.n_stages):
+            tau = plan.stage_effective_staleness(j)
+            window = host[j].versions[len(host[j].versions) - 1 - tau:]
+            ref = O.accumulate_stage(window, host[j].grads, None, w.n_iters, np.float32(w.lam), np.float32(w.lr),
+                                     np.float32(0.5), last, acc_host[j])
+            tag = f"arrival {k} stage {j}"
+            PU.assert_close_f32(st.get_flat(st.grad_out, j).numpy(), ref["g"], tag + " g")
+            got_acc = st.get_flat(accum, j).numpy()
+            PU.assert_close_f32(got_acc, ref["accum"], tag + " accum")
+            acc_host[j] = got_acc.copy()
+            if last:
+                PU.assert_close_f32(st.get_version(j, plan.stage_write_slot(j)).numpy(), ref["new"], tag + " version")

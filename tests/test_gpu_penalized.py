@@ -67,3 +67,25 @@ def test_unit_penalty_is_the_uncompensated_step_bit_for_bit():
     torch.cuda.synchronize()
     for j in range(2):
         assert torch.equal(st.get_version(j, plan.stage_write_slot(j)), want[j])
+
+
+@pytest.mark.parametrize("method", ["step-aware", "gap-aware"])
+def test_penalized_step_at_benchmark_shape(method):
+    """ViT-B-sized workload, the launch configuration bench.py --compensator step-aware / gap-aware times."""
+    w = W.make_workload(4)
+    plan, st, host = PU.load_workload(w, amplified=True)
+    gap = method == "gap-aware"
+    scale = [1.0] * w.n_stages if gap else None
+    inv_c = [1.0 / (w.lr * w.grad_std)] * w.n_stages if gap else None
+    B.ferret_penalized_step(plan, st.ring, st.grads, st.master, scale, inv_c, w.lr, st.norms, st.grad_out, st.workspace)
+    torch.cuda.synchronize()
+    for j in range(w.n_stages):
+        d = host[j]
+        t = plan.stage_effective_staleness(j)
+        sc = np.float32(1.0) / np.float32(max(t, 1)) if scale is None else np.float32(scale[j])
+        ic = np.float32(0.0) if inv_c is None else np.float32(inv_c[j])
+        ref = O.penalized_stage(d.versions[len(d.versions) - 1 - t], d.versions[-1], d.grads, None, np.float32(w.lr),
+                                sc, ic)
+        tag = f"{method} stage {j}"
+        PU.assert_close_f32(st.get_flat(st.grad_out, j).numpy(), ref["g"], tag + " penalised gradient")
+        PU.assert_close_f32(st.get_version(j, plan.stage_write_slot(j)).numpy(), ref["new"], tag + " version")
