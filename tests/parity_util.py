@@ -42,7 +42,8 @@ def assert_close_f32(got, ref, what):
     worst = int(np.argmax(err - bound))
     assert np.all(err <= bound), (f"{what}: {int((err > bound).sum())} of {err.size} elements out of tolerance; "
                                   f"worst got {got[finite][worst]!r} ref {ref[finite][worst]!r}")
-    return float((err / np.maximum(np.abs(ref[finite]), rms)).max())
+    den = np.maximum(np.abs(ref[finite]), rms)
+    return float((err / np.where(den > 0, den, 1.0)).max())       # an all-zero reference has err = 0 as well
 
 
 def bf16_ulp_distance(a_bits, b_bits):
