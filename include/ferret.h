@@ -297,7 +297,7 @@ ferret_status ferret_accumulate_step(const ferret_plan *plan, void *ring, const 
  * "update lambda" block of ferret_compensate_step_adaptive on this gradient (V[0], V[1] counted from
  * the version THIS gradient was taken on), then compensates with the new lambda_j and accumulates as
  * ferret_accumulate_step does.  Stages with mode 0 keep lambda_j, v_r, v_a untouched.
- * adaptive->fused must be 0 (FERRET_EINVAL otherwise); `workspace` is required. */
+ * adaptive->fused selects the order as in ferret_compensate_step_adaptive; `workspace` is required. */
 ferret_status ferret_accumulate_step_adaptive(const ferret_plan *plan, void *ring, const void *grads,
                                               float *master, const ferret_accumulate *accumulate,
                                               const ferret_adaptive *adaptive, float lr, float *norms_out,

@@ -247,17 +247,20 @@ def accumulate_stage(versions, g0, master, K: int, lam: float, eta: float, scale
 
 
 def accumulate_stage_adaptive(versions, g0, master, K: int, lam: float, alpha: float, eta_lambda: float, eta: float,
-                              scale: float, do_update: bool, accum, v_r, v_a, bf16: bool = False):
+                              scale: float, do_update: bool, accum, v_r, v_a, bf16: bool = False,
+                              lambda_step_last: bool = False):
     """One arriving gradient under accumulation with self-tuned lambda: Alg. 1 runs per gradient, so the
     lambda block comes first (on the version this gradient was taken on and the one after it; skipped when
-    eta_lambda = 0 or the arrival has no staleness), then accumulate_stage with the new lambda."""
+    eta_lambda = 0 or the arrival has no staleness), then accumulate_stage with the new lambda
+    (lambda_step_last: with the lambda that was passed in, as in compensate_stage_adaptive)."""
     tau = len(versions) - 1
     if eta_lambda > 0 and tau >= 1:
         lam_new, r_new, a_new, _ = lambda_update(g0, versions[0], versions[1], lam, alpha, eta_lambda, v_r, v_a, bf16)
     else:
         lam_new = float(lam)
         r_new, a_new = _as_np(v_r, np.float32).copy(), _as_np(v_a, np.float32).copy()
-    out = accumulate_stage(versions, g0, master, K, lam_new, eta, scale, do_update, accum, bf16)
+    lam_used = float(lam) if lambda_step_last else lam_new
+    out = accumulate_stage(versions, g0, master, K, lam_used, eta, scale, do_update, accum, bf16)
     out.update(lam=lam_new, v_r=r_new, v_a=a_new)
     return out
 

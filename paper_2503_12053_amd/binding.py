@@ -252,12 +252,12 @@ def ferret_accumulate_step(plan: "Plan", ring, grads, master, accum, scale: floa
 def ferret_accumulate_step_adaptive(plan: "Plan", ring, grads, master, accum, scale: float, mode: Sequence[int],
                                     staleness: Optional[Sequence[int]], lambda_dev, v_r, v_a, alpha: float,
                                     eta_lambda: float, lr: float, norms_out=None, grad_out=None, workspace=None,
-                                    stream=None) -> None:
+                                    stream=None, fused: bool = False) -> None:
     P = plan.n_stages
     mode_arr = (c_int32 * P)(*[int(m) for m in mode])
     st_arr = (c_int32 * P)(*[int(x) for x in staleness]) if staleness is not None else None
     acc = ferret_accumulate(_ptr(accum), scale, mode_arr, st_arr)
-    ad = ferret_adaptive(_ptr(lambda_dev), _ptr(v_r), _ptr(v_a), alpha, eta_lambda, 0, 0)
+    ad = ferret_adaptive(_ptr(lambda_dev), _ptr(v_r), _ptr(v_a), alpha, eta_lambda, int(fused), 0)
     _check(load().ferret_accumulate_step_adaptive(plan.handle, _ptr(ring), _ptr(grads), _ptr(master), byref(acc),
                                                   byref(ad), lr, _ptr(norms_out), _ptr(grad_out), _ptr(workspace),
                                                   _stream(stream)))

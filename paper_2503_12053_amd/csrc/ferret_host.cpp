@@ -519,7 +519,6 @@ static ferret_status accumulate_impl(const char *who, const ferret_plan *plan, v
     if (ad) {
         rc = check_adaptive(who, plan, ad, workspace);
         if (rc != FERRET_OK) return rc;
-        if (ad->fused) { set_error("%s: the one-pass lambda block is not available with accumulation (fused must be 0)", who); return FERRET_EINVAL; }
     }
     if (!acc || !acc->accum || !acc->mode) { set_error("%s: null accumulate, accum or mode", who); return FERRET_EINVAL; }
     if (!aligned16(acc->accum)) { set_error("%s: accum must be 16-byte aligned", who); return FERRET_EINVAL; }
@@ -549,7 +548,10 @@ static ferret_status accumulate_impl(const char *who, const ferret_plan *plan, v
     int err = 0;
     if (ad) {
         set_adaptive_args(a, ad);
-        if (ad->eta_lambda > 0.f) {      // lambda block of every participating stage, on this arrival's staleness
+        if (ad->eta_lambda > 0.f && ad->fused) {
+            a.fused_lambda = 1;          // one pass: the accumulation kernel runs the lambda block too
+            a.partials = static_cast<float *>(workspace);
+        } else if (ad->eta_lambda > 0.f) {      // lambda block of every participating stage, on this arrival's staleness
             float *step_partials = a.partials;
             a.partials = static_cast<float *>(workspace);
             err = launch_lambda_update(*plan, a, hip_stream);

@@ -1102,6 +1102,18 @@ static hipError_t launch_step_accum(const StepArgs &a, bool norms, bool gout, ui
     return hipGetLastError();
 }
 
+// Accumulation with the "update lambda" block fused in.
+template <typename S>
+static hipError_t launch_step_accum_fused(const StepArgs &a, bool norms, bool gout, uint32_t grid, uint32_t dyn_lds,
+                                          hipStream_t st) {
+#define FERRET_LAUNCH(NO, OUT) \
+    hipLaunchKernelGGL((step_kernel<S, false, 2, NO, OUT>), dim3(grid), dim3(kThreads), dyn_lds, st, a)
+    if (norms) { if (gout) FERRET_LAUNCH(true, 19); else FERRET_LAUNCH(true, 18); }
+    else       { if (gout) FERRET_LAUNCH(false, 19); else FERRET_LAUNCH(false, 18); }
+#undef FERRET_LAUNCH
+    return hipGetLastError();
+}
+
 template <typename S, bool PERSISTENT>
 static hipError_t launch_step_typed(const StepArgs &a, int level, bool norms, bool gout, bool elide, uint32_t grid,
                                     uint32_t dyn_lds, hipStream_t st) {
@@ -1120,6 +1132,7 @@ struct StepLaunch {
 
 template <typename S>
 static hipError_t launch_step_for(const StepArgs &a, const StepLaunch &l, hipStream_t st) {
+    if (a.fused_lambda && a.accum) return launch_step_accum_fused<S>(a, l.norms, l.gout, l.chunks, l.lds, st);
     if (a.fused_lambda) return launch_step_fused<S>(a, l.level, l.norms, l.gout, l.chunks, l.lds, st);
     if (a.penalized) return launch_step_penalized<S>(a, l.norms, l.gout, l.chunks, l.lds, st);
     if (a.accum) return launch_step_accum<S>(a, l.norms, l.gout, l.chunks, l.lds, st);

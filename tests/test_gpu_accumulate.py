@@ -119,8 +119,9 @@ def test_skipped_stage_is_left_alone():
     assert e.value.status == B.FERRET_ESTATE
 
 
+@pytest.mark.parametrize("fused", [False, True])
 @pytest.mark.parametrize("precision", ["f32", "bf16"])
-def test_accumulation_with_self_tuned_lambda(precision):
+def test_accumulation_with_self_tuned_lambda(precision, fused):
     """Per-arrival lambda block + accumulation over several groups: lambda_j, v_r, v_a, the running sum and the
     versions follow the oracle; a skipped stage keeps its lambda and averages."""
     ca, tau_max = [2, 3, 1], [2, 1, 0]
@@ -153,7 +154,8 @@ def test_accumulation_with_self_tuned_lambda(precision):
             host[j].grads = g
         write_slots = [plan.stage_write_slot(j) for j in range(3)]
         B.ferret_accumulate_step_adaptive(plan, st.ring, st.grads, st.master, accum, scale, mode, stale, st.lambda_dev,
-                                          st.v_r, st.v_a, alpha, eta_l, w.lr, st.norms, st.grad_out, st.workspace)
+                                          st.v_r, st.v_a, alpha, eta_l, w.lr, st.norms, st.grad_out, st.workspace,
+                                          fused=fused)
         torch.cuda.synchronize()
         lam_gpu = st.lambda_dev.cpu().numpy()
         for j in range(3):
@@ -168,7 +170,7 @@ def test_accumulation_with_self_tuned_lambda(precision):
             window = versions[j][len(versions[j]) - 1 - tau:]
             ref = O.accumulate_stage_adaptive(window, host[j].grads, master[j], -1, lams[j], np.float32(alpha),
                                               np.float32(eta_l), np.float32(w.lr), np.float32(scale), mode[j] == 2,
-                                              acc_host[j], state[j][0], state[j][1], bf16=bf16)
+                                              acc_host[j], state[j][0], state[j][1], bf16=bf16, lambda_step_last=fused)
             assert lam_gpu[j] == pytest.approx(ref["lam"], rel=1e-5), tag + " lambda"
             if tau == 0:
                 assert lam_gpu[j] == lams[j], tag
@@ -192,43 +194,3 @@ def test_accumulation_with_self_tuned_lambda(precision):
                 versions[j] = (versions[j] + [got_new])[-plan.stage_ring_depth(j):]
                 B.ferret_push_version(plan, st.ring, None, j, None)
     assert lams[0] != np.float32(w.lam) and lams[2] == np.float32(w.lam)
-
-
-def test_accumulation_with_lambda_rejects_the_one_pass_order():
-    w = W.custom_workload("accumulate_adaptive_bad", [[4_096]], [1], 2, -1, seed=55)
-    plan, st, host = PU.load_workload(w, amplified=True)
-    st.enable_adaptive(w.lam)
-    accum = torch.zeros(plan.flat_elems, device="cuda")
-    acc = B.ferret_accumulate(B._ptr(accum), 1.0, (B.c_int32 * 1)(2), None)
-    ad = B.ferret_adaptive(B._ptr(st.lambda_dev), B._ptr(st.v_r), B._ptr(st.v_a), 0.9, 1e-3, 1, 0)
-    rc = B.load().ferret_accumulate_step_adaptive(plan.handle, B._ptr(st.ring), B._ptr(st.grads), None, B.byref(acc),
-                                                  B.byref(ad), 0.01, None, None, B._ptr(st.workspace), None)
-    assert rc == B.FERRET_EINVAL and "fused" in B.last_error()
-
-
-def test_accumulation_at_benchmark_shape():
-    """ViT-B-sized workload, the launch configuration bench.py --accumulate 2 times: two arrivals per stage, the
-    second one updates."""
-    w = W.make_workload(4)
-    plan, st, host = PU.load_workload(w, amplified=True)
-    accum = torch.zeros(plan.flat_elems, device="cuda")
-    acc_host = [np.zeros(n, np.float32) for n in w.stage_numel()]
-    for k in range(2):
-        last = k == 1
-        for j in range(w.n_stages):
-            g = W.draw_grads(w, j, w.stage_numel()[j], amplified=True, step=k)
-            st.set_flat(st.grads, j, g)
-            host[j].grads = g
-        _accum_call(plan, st, accum, 0.5, [2 if last else 1] * w.n_stages, None, w.lam, w.lr)
-        for j in range(w.n_stages):
-            tau = plan.stage_effective_staleness(j)
-            window = host[j].versions[len(host[j].versions) - 1 - tau:]
-            ref = O.accumulate_stage(window, host[j].grads, None, w.n_iters, np.float32(w.lam), np.float32(w.lr),
-                                     np.float32(0.5), last, acc_host[j])
-            tag = f"arrival {k} stage {j}"
-            PU.assert_close_f32(st.get_flat(st.grad_out, j).numpy(), ref["g"], tag + " g")
-            got_acc = st.get_flat(accum, j).numpy()
-            PU.assert_close_f32(got_acc, ref["accum"], tag + " accum")
-            acc_host[j] = got_acc.copy()
-            if last:
-                PU.assert_close_f32(st.get_version(j, plan.stage_write_slot(j)).numpy(), ref["new"], tag + " version")
