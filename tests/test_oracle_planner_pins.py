@@ -2,11 +2,20 @@
 deltas where they are printed intact, and brute force on tiny instances."""
 import itertools
 import math
+import os
 import random
 
 import pytest
 
-from oracle import planner_oracle as PO
+if os.environ.get("FERRET_PLANNER_ORACLE"):      # the mutation tests point the pins at a modified copy
+    import importlib.util
+    _spec = importlib.util.spec_from_file_location("planner_oracle_under_test", os.environ["FERRET_PLANNER_ORACLE"])
+    PO = importlib.util.module_from_spec(_spec)
+    import sys
+    sys.modules[_spec.name] = PO
+    _spec.loader.exec_module(PO)
+else:
+    from oracle import planner_oracle as PO
 
 
 def _layers(rng, n):
@@ -47,6 +56,36 @@ def test_hand_computed_two_stage_one_worker():
     b00 = math.exp(-0.1 * (4 + 6 + 2 * 2)) * 5 / 7
     b10 = math.exp(-0.1 * (4 + 3 + 1 * 2)) * 5 / 7
     assert R1 == pytest.approx(0.75 * b00 + 0.25 * b10, rel=1e-14) and M1 == M
+
+
+def test_hand_computed_omission_slows_every_earlier_stage():
+    """P = 3, one worker, stage 1 updated only every third gradient (c^o_1 = 2): the update frequency of stage i
+    is divided by lcm(c^o_k + 1, k >= i) = (3, 3, 1), because back-propagation that stops at stage 1 never reaches
+    stage 0 either.  t^f = 1, t^b = 2, c = 0.1, V = 6, equal stage weights:
+        A_{i,0} = exp(-c (3 t^f + (3 - i) t^b)) V / (lcm_i (t^f + t^b))
+        R = (A_00 + A_10 + A_20) / 3 = (e^-0.9 / 3 + e^-0.7 / 3 + e^-0.5) 2 / 3
+    and stage 1 keeps 1 + (P-1-1) - c^o_1 = 0 extra copies: versions (3, 0, 1)."""
+    layers = [PO.Layer(1.0, 2.0, 10.0, 1.0)] * 3
+    S = PO.stages_of(layers, [0, 1, 2, 3])
+    C = PO.Config([0], [0], [[1, 1, 1]], [[0, 2, 0]])
+    R, M = PO.evaluate(S, C, 0.1, 6.0)
+    want = (math.exp(-0.9) / 3 + math.exp(-0.7) / 3 + math.exp(-0.5)) * 2 / 3
+    assert R == pytest.approx(want, rel=1e-14)
+    assert M == (3 + 0 + 1) * 11
+
+
+def test_greedy_takes_the_move_that_saves_most_memory_per_rate_lost():
+    """P = 3, one worker, three equal stages, budget just below the full footprint.  Two moves apply: S2 on
+    stage 0 (accumulate two gradients: one version less, rate of stage 0 from A_00 to (A_00 + A_01)/2, a loss
+    of a few per cent for small c) and S3 on stage 1 (omit every other backward pass: one version less, but the
+    rates of stages 0 AND 1 are halved).  Both free the same memory, so Alg. 2 must take S2."""
+    layers = [PO.Layer(1.0, 2.0, 10.0, 1.0)] * 3
+    S = PO.stages_of(layers, [0, 1, 2, 3])
+    full = PO.evaluate(S, PO.Config([0], [0], [[1, 1, 1]], [[0, 0, 0]]), 0.01, 1.0)
+    assert full[1] == (3 + 2 + 1) * 11
+    C, R, Mem, trace = PO.itersearch(S, 3.0, 0, full[1] - 1.0, 0.01, 1.0)
+    assert trace == [(0, "S2", 0)] and Mem == full[1] - 11
+    assert R > 0.95 * full[0]
 
 
 def test_stage_aggregates_and_recompute_saving():
