@@ -192,6 +192,12 @@ def test_version_order_matters():
     assert g_rev[0] == pytest.approx(2.00539395, rel=1e-6)
 
 
+def test_without_iterations_only_the_newest_version_is_a_boundary():
+    """K' = 0 leaves only Alg. 1's update line, which reads the current weights V[tau] and nothing else."""
+    assert O.segment_boundaries(5, 0) == [5]
+    assert O.segment_boundaries(0, 3) == [0] and O.segment_boundaries(0, -1) == [0]
+
+
 def test_update_uses_newest_version():
     V = [[10.0], [20.0], [30.0]]
     new, _, norms = _stage(V, [0.0], -1, 0.5, 0.01)
