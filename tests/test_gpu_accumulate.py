@@ -194,3 +194,86 @@ def test_accumulation_with_self_tuned_lambda(precision, fused):
                 versions[j] = (versions[j] + [got_new])[-plan.stage_ring_depth(j):]
                 B.ferret_push_version(plan, st.ring, None, j, None)
     assert lams[0] != np.float32(w.lam) and lams[2] == np.float32(w.lam)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_accumulation_schedules(seed):
+    """Random stages, sizes, ring depths, iteration counts, chunk sizes and per-call (mode, staleness) patterns,
+    with and without the self-tuned lambda (either ordering); every call is compared with the oracle."""
+    rng = np.random.default_rng(5000 + seed)
+    P = int(rng.integers(1, 5))
+    tau_max = [int(rng.integers(0, 4)) for _ in range(P)]
+    sizes = [[int(rng.choice([8, 63, 500, 1024, 2049, 7000]) * rng.integers(1, 4)) for _ in range(int(rng.integers(1, 3)))]
+             for _ in range(P)]
+    K = int(rng.choice([-1, 1, 2]))
+    bf16 = bool(seed % 2)
+    adaptive = (seed // 2) % 3            # 0: fixed lambda, 1: Alg. 1's order, 2: one pass
+    w = W.custom_workload(f"random_accum{seed}", sizes, tau_max, max(tau_max) + 1, K,
+                          precision="bf16" if bf16 else "f32", seed=6000 + seed, lam=0.3, lr=0.05)
+    plan, st, host = PU.load_workload(w, amplified=True, ring_depth=B.FERRET_RING_DEPTH_MINIMAL,
+                                      chunk_elems=int(rng.choice([0, 1024, 4096])))
+    if adaptive:
+        st.enable_adaptive(w.lam)
+    n = w.stage_numel()
+    accum = torch.zeros(plan.flat_elems, device="cuda")
+    acc_host = [np.zeros(k, np.float32) for k in n]
+    state = [(np.zeros(k, np.float32), np.zeros(k, np.float32)) for k in n]
+    lams = [np.float32(w.lam)] * P
+    versions = [list(d.versions) for d in host]
+    master = [None if d.master is None else d.master.numpy().copy() for d in host]
+    alpha, eta_l, scale = 0.5, 1e-3, float(rng.choice([1.0, 0.5]))
+    for m in range(6):
+        mode = [int(rng.choice([0, 1, 1, 2])) for _ in range(P)]
+        stale = [int(rng.integers(0, tau_max[j] + 1)) for j in range(P)]
+        for j in range(P):
+            g = W.draw_grads(w, j, n[j], amplified=True, step=m)
+            g = g.to(torch.bfloat16) if bf16 else g
+            st.set_flat(st.grads, j, g)
+            host[j].grads = g
+        write_slots = [plan.stage_write_slot(j) for j in range(P)]
+        if adaptive:
+            B.ferret_accumulate_step_adaptive(plan, st.ring, st.grads, st.master, accum, scale, mode, stale,
+                                              st.lambda_dev, st.v_r, st.v_a, alpha, eta_l, w.lr, st.norms, st.grad_out,
+                                              st.workspace, fused=adaptive == 2)
+        else:
+            B.ferret_accumulate_step(plan, st.ring, st.grads, st.master, accum, scale, mode, stale, w.lam, w.lr,
+                                     st.norms, st.grad_out, st.workspace)
+        torch.cuda.synchronize()
+        lam_gpu = st.lambda_dev.cpu().numpy() if adaptive else None
+        for j in range(P):
+            tag = f"seed {seed} call {m} stage {j} mode {mode[j]}"
+            got_acc = st.get_flat(accum, j).numpy()
+            if mode[j] == 0:
+                assert np.array_equal(got_acc, acc_host[j]), tag
+                continue
+            tau = min(stale[j], len(versions[j]) - 1)
+            window = versions[j][len(versions[j]) - 1 - tau:]
+            if adaptive:
+                ref = O.accumulate_stage_adaptive(window, host[j].grads, master[j], K, lams[j], np.float32(alpha),
+                                                  np.float32(eta_l), np.float32(w.lr), np.float32(scale), mode[j] == 2,
+                                                  acc_host[j], state[j][0], state[j][1], bf16=bf16,
+                                                  lambda_step_last=adaptive == 2)
+                assert lam_gpu[j] == pytest.approx(ref["lam"], rel=1e-5), tag + " lambda"
+                got_r, got_a = st.get_flat(st.v_r, j).numpy(), st.get_flat(st.v_a, j).numpy()
+                PU.assert_close_f32(got_r, ref["v_r"], tag + " v_r")
+                PU.assert_close_f32(got_a, ref["v_a"], tag + " v_a")
+                state[j], lams[j] = (got_r.copy(), got_a.copy()), lam_gpu[j]
+            else:
+                ref = O.accumulate_stage(window, host[j].grads, master[j], K, np.float32(w.lam), np.float32(w.lr),
+                                         np.float32(scale), mode[j] == 2, acc_host[j], bf16=bf16)
+            PU.assert_close_f32(st.get_flat(st.grad_out, j).numpy(), ref["g"], tag + " g")
+            PU.assert_close_f32(got_acc, ref["accum"], tag + " accum")
+            acc_host[j] = got_acc.copy()
+            if mode[j] == 2:
+                got_new = st.get_version(j, write_slots[j])
+                if bf16:
+                    got_m = st.get_flat(st.master, j).numpy()
+                    PU.assert_close_f32(got_m, ref["master"], tag + " master")
+                    rms = float(np.sqrt(np.mean(ref["master"].astype(np.float64) ** 2)))
+                    PU.assert_bf16_within_one_ulp(PU.bits_of(got_new), ref["new"], tag + " version",
+                                                  abs_slack=PU.RTOL * rms)
+                    master[j] = got_m.copy()
+                else:
+                    PU.assert_close_f32(got_new.numpy(), ref["new"], tag + " version")
+                versions[j] = (versions[j] + [got_new])[-plan.stage_ring_depth(j):]
+                B.ferret_push_version(plan, st.ring, None, j, None)
