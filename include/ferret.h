@@ -262,6 +262,12 @@ ferret_status ferret_compensate_step_adaptive(const ferret_plan *plan, void *rin
                                               float *master, const ferret_adaptive *adaptive, float lr,
                                               float *norms_out, void *grad_out, void *workspace,
                                               void *hip_stream);
+/* The same for the stages j with active[j] != 0 only (host int32[n_stages]), as ferret_compensate_stages is to
+ * ferret_compensate_step: stages left out keep their weights, lambda_j, v_r and v_a, and have nothing to commit. */
+ferret_status ferret_compensate_stages_adaptive(const ferret_plan *plan, void *ring, const void *grads,
+                                                float *master, const int32_t *active,
+                                                const ferret_adaptive *adaptive, float lr, float *norms_out,
+                                                void *grad_out, void *workspace, void *hip_stream);
 
 /* ---- gradient accumulation (T2) -------------------------------------------------------------- */
 /* Sec. "Fine-grained Pipeline Parallelism", T2: with c^a accumulation steps a stage applies one

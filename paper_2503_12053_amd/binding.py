@@ -104,6 +104,8 @@ SIGNATURES = {
     "ferret_push_version": (c_int32, [_P, _P, _P, c_int32, _P, _P]),
     "ferret_compensate_step": (c_int32, [_P, _P, _P, _P, c_float, c_float, _P, _P, _P, _P]),
     "ferret_compensate_step_adaptive": (c_int32, [_P, _P, _P, _P, POINTER(ferret_adaptive), c_float, _P, _P, _P, _P]),
+    "ferret_compensate_stages_adaptive": (c_int32, [_P, _P, _P, _P, POINTER(c_int32), POINTER(ferret_adaptive), c_float,
+                                                    _P, _P, _P, _P]),
     "ferret_compensate_stages": (c_int32, [_P, _P, _P, _P, POINTER(c_int32), c_float, c_float, _P, _P, _P, _P]),
     "ferret_accumulate_step": (c_int32, [_P, _P, _P, _P, POINTER(ferret_accumulate), c_float, c_float, _P, _P, _P, _P]),
     "ferret_accumulate_step_adaptive": (c_int32, [_P, _P, _P, _P, POINTER(ferret_accumulate), POINTER(ferret_adaptive),
@@ -236,6 +238,16 @@ def ferret_compensate_stages(plan: "Plan", ring, grads, master, active: Sequence
     arr = (c_int32 * plan.n_stages)(*[int(bool(x)) for x in active])
     _check(load().ferret_compensate_stages(plan.handle, _ptr(ring), _ptr(grads), _ptr(master), arr, lam, lr,
                                            _ptr(norms_out), _ptr(grad_out), _ptr(workspace), _stream(stream)))
+
+
+def ferret_compensate_stages_adaptive(plan: "Plan", ring, grads, master, active: Sequence[int], lambda_dev, v_r, v_a,
+                                      alpha: float, eta_lambda: float, lr: float, norms_out=None, grad_out=None,
+                                      workspace=None, stream=None, fused: bool = False) -> None:
+    arr = (c_int32 * plan.n_stages)(*[int(bool(x)) for x in active])
+    ad = ferret_adaptive(_ptr(lambda_dev), _ptr(v_r), _ptr(v_a), alpha, eta_lambda, int(fused), 0)
+    _check(load().ferret_compensate_stages_adaptive(plan.handle, _ptr(ring), _ptr(grads), _ptr(master), arr, byref(ad),
+                                                    lr, _ptr(norms_out), _ptr(grad_out), _ptr(workspace),
+                                                    _stream(stream)))
 
 
 def ferret_accumulate_step(plan: "Plan", ring, grads, master, accum, scale: float, mode: Sequence[int],

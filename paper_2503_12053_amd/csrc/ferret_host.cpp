@@ -482,11 +482,9 @@ ferret_status ferret_compensate_stages(const ferret_plan *plan, void *ring, cons
     return FERRET_OK;
 }
 
-ferret_status ferret_compensate_step_adaptive(const ferret_plan *plan, void *ring, const void *grads,
-                                              float *master, const ferret_adaptive *ad, float lr,
-                                              float *norms_out, void *grad_out, void *workspace,
-                                              void *hip_stream) {
-    const char *who = "compensate_step_adaptive";
+static ferret_status adaptive_impl(const char *who, const ferret_plan *plan, void *ring, const void *grads,
+                                   float *master, const int32_t *active, const ferret_adaptive *ad, float lr,
+                                   float *norms_out, void *grad_out, void *workspace, void *hip_stream) {
     ferret_status rc = check_step_args(who, plan, ring, grads, master, norms_out, grad_out, workspace);
     if (rc != FERRET_OK) return rc;
     rc = check_adaptive(who, plan, ad, workspace);
@@ -494,6 +492,11 @@ ferret_status ferret_compensate_step_adaptive(const ferret_plan *plan, void *rin
     StepArgs a;
     fill_step_args(plan, a, ring, grads, master, 0.f, lr, norms_out, grad_out, workspace);
     set_adaptive_args(a, ad);
+    if (active) {
+        a.masked = 1;
+        for (size_t j = 0; j < plan->stages.size(); ++j) a.mode[j] = active[j] ? 2 : 0;
+        narrow_chunk_span(plan, a);
+    }
     int err = 0;
     if (ad->eta_lambda > 0.f && ad->fused) {
         a.fused_lambda = 1;                                // one pass: the step kernel runs the lambda block too
@@ -506,8 +509,26 @@ ferret_status ferret_compensate_step_adaptive(const ferret_plan *plan, void *rin
     }
     if (!err) err = launch_step(*plan, a, norms_out, hip_stream);
     if (err) { set_error("%s: launch failed: %s", who, device_error_string(err)); return FERRET_EDEVICE; }
-    for (const Stage &s : plan->stages) s.step_pending = true;
+    for (size_t j = 0; j < plan->stages.size(); ++j)
+        if (!active || active[j]) plan->stages[j].step_pending = true;
     return FERRET_OK;
+}
+
+ferret_status ferret_compensate_step_adaptive(const ferret_plan *plan, void *ring, const void *grads,
+                                              float *master, const ferret_adaptive *ad, float lr,
+                                              float *norms_out, void *grad_out, void *workspace,
+                                              void *hip_stream) {
+    return adaptive_impl("compensate_step_adaptive", plan, ring, grads, master, nullptr, ad, lr, norms_out, grad_out,
+                         workspace, hip_stream);
+}
+
+ferret_status ferret_compensate_stages_adaptive(const ferret_plan *plan, void *ring, const void *grads,
+                                                float *master, const int32_t *active, const ferret_adaptive *ad,
+                                                float lr, float *norms_out, void *grad_out, void *workspace,
+                                                void *hip_stream) {
+    if (!active) { set_error("compensate_stages_adaptive: null active"); return FERRET_EINVAL; }
+    return adaptive_impl("compensate_stages_adaptive", plan, ring, grads, master, active, ad, lr, norms_out, grad_out,
+                         workspace, hip_stream);
 }
 
 static ferret_status accumulate_impl(const char *who, const ferret_plan *plan, void *ring, const void *grads,

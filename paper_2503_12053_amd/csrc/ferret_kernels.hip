@@ -750,7 +750,7 @@ constexpr int kLambdaThreads = 1024;
 __global__ void __launch_bounds__(kLambdaThreads) lambda_step_kernel(const StepArgs a) {
     __shared__ double red[2][kLambdaThreads / 64];
     const uint32_t j = blockIdx.x;
-    if (a.stage[j].tau == 0 || (a.accum && a.mode[j] == 0)) return;     // nothing to tune, or no gradient arrived
+    if (a.stage[j].tau == 0 || ((a.accum || a.masked) && a.mode[j] == 0)) return;     // nothing to tune, or no gradient arrived
     const uint32_t c0 = a.stage[j].chunk_begin;
     const uint32_t c1 = j + 1 < a.n_stages ? a.stage[j + 1].chunk_begin : a.n_chunks;
     // the two series: 0 and 1 when the state pass produced them, 3 and 4 when the fused step did
@@ -1210,7 +1210,7 @@ int launch_lambda_update(const ferret_plan &plan, const StepArgs &a, void *strea
         const uint64_t per = (plan.prec == FERRET_F32 ? 4u : 2u) * 3u + 16u;
         uint64_t bytes = 0;
         for (uint32_t j = 0; j < a.n_stages; ++j)
-            if (a.stage[j].tau >= 1 && !(a.accum && a.mode[j] == 0)) bytes += a.stage[j].n_elems * per;
+            if (a.stage[j].tau >= 1 && !((a.accum || a.masked) && a.mode[j] == 0)) bytes += a.stage[j].n_elems * per;
         const int32_t env = plan.resident_cap;
         int32_t cap = env != 0 ? env : (bytes > kCapThresholdBytes
                                             ? (int32_t)((kStateTargetBytes + a.chunk_elems * per - 1) / (a.chunk_elems * per)) : -1);

@@ -191,3 +191,36 @@ def test_random_adaptive_configurations(seed):
     st.step_adaptive(alpha, eta_l, w.lr, fused=fused)
     torch.cuda.synchronize()
     _check(w, plan, st, host, state, [w.lam] * n_stages, alpha, eta_l, K, f"seed {seed} fused={fused}", fused)
+
+
+@pytest.mark.parametrize("fused", [False, True])
+@pytest.mark.parametrize("active", [[1, 0, 1, 0], [0, 1, 0, 0], [0, 0, 0, 0]])
+def test_adaptive_step_for_a_subset_of_stages(fused, active):
+    """Stages that take part end up exactly as after the full self-tuned step; the others keep weights, lambda
+    and averages."""
+    w = W.custom_workload("adaptive_subset", [[30_000, 8], [12_345], [9_000], [4_096]], [3, 2, 1, 1], 4, 2, seed=37,
+                          lam=0.3)
+    plan, st, host = PU.load_workload(w, amplified=True)
+    _state(w, st, 37, w.lam)
+    st.step_adaptive(0.8, 1e-3, w.lr, fused=fused)
+    torch.cuda.synchronize()
+    full = dict(ring=st.ring.clone(), lam=st.lambda_dev.clone(), vr=st.v_r.clone(), va=st.v_a.clone(),
+                norms=st.norms.clone(), g=st.grad_out.clone())
+    plan2, st2, _ = PU.load_workload(w, amplified=True)
+    _state(w, st2, 37, w.lam)
+    before = dict(ring=st2.ring.clone(), lam=st2.lambda_dev.clone(), vr=st2.v_r.clone(), va=st2.v_a.clone())
+    B.ferret_compensate_stages_adaptive(plan2, st2.ring, st2.grads, st2.master, active, st2.lambda_dev, st2.v_r, st2.v_a,
+                                        0.8, 1e-3, w.lr, st2.norms, st2.grad_out, st2.workspace, fused=fused)
+    torch.cuda.synchronize()
+    for j in range(4):
+        lo = plan2.stage_ring_offset(j)
+        hi = lo + plan2.stage_slot_stride(j) * plan2.stage_ring_depth(j)
+        f0, f1 = plan2.stage_flat_offset(j), plan2.stage_flat_offset(j) + plan2.stage_numel(j)
+        ref = full if active[j] else before
+        assert torch.equal(st2.ring[lo:hi], ref["ring"][lo:hi]), f"stage {j} ring"
+        assert torch.equal(st2.lambda_dev[j], ref["lam"][j]), f"stage {j} lambda"
+        assert torch.equal(st2.v_r[f0:f1], ref["vr"][f0:f1]) and torch.equal(st2.v_a[f0:f1], ref["va"][f0:f1])
+        if active[j]:
+            assert torch.equal(st2.norms[j], full["norms"][j]) and torch.equal(st2.grad_out[f0:f1], full["g"][f0:f1])
+        else:
+            assert not st2.norms[j].any()
