@@ -209,6 +209,23 @@ ferret_status ferret_compensate_step(const ferret_plan *plan, void *ring, const 
                                      float *master, float lambda, float lr, float *norms_out,
                                      void *grad_out, void *workspace, void *hip_stream);
 
+/* ferret_compensate_step for callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments minus
+ * `workspace`, same kernels, bit-identical results; the per-chunk partial sums of the norms go through a
+ * fixed array of FERRET_NOALLOC_MAX_CHUNKS * 20 bytes (5 MiB) that is part of the library's device code
+ * (each GPU the library runs on holds it until the process ends).  The call allocates nothing, on the host
+ * or the device, and neither does anything it calls; on its first use on a device it looks the array's
+ * address up once (hipGetSymbolAddress, with that device current), so make that first call outside a
+ * graph capture.  The device current on the calling thread must be the one that owns the buffers and the
+ * stream.  FERRET_EINVAL if the plan has more than FERRET_NOALLOC_MAX_CHUNKS chunks (plan with a larger
+ * chunk_elems, or use ferret_compensate_step).  All calls on one GPU share the one array: calls that
+ * overlap in time on the same GPU (different streams or threads) race on it when norms_out is given;
+ * with norms_out == NULL the array is not touched. */
+#define FERRET_NOALLOC_MAX_CHUNKS 262144
+ferret_status ferret_compensate_step_noalloc(const ferret_plan *plan, void *ring, const void *grads,
+                                             float *master, float lambda, float lr, float *norms_out,
+                                             void *grad_out, void *hip_stream);
+
 /* The same step for some of the plan's stages only (in a pipeline the gradients of different stages
  * arrive at different times): stage j takes part iff active[j] != 0 (host int32[n_stages]).  Stages
  * left out are not read or written, their norms_out rows read 0, and they have nothing to commit.

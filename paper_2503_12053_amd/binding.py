@@ -27,6 +27,7 @@ FERRET_ITERS_FULL = -1
 FERRET_RING_DEPTH_MINIMAL = 0
 FERRET_MAX_STAGES = 64
 FERRET_ALIGN_ELEMS = 8
+FERRET_NOALLOC_MAX_CHUNKS = 262144
 
 STATUS_NAMES = {0: "FERRET_OK", 1: "FERRET_EINVAL", 2: "FERRET_ESTATE", 3: "FERRET_ENOMEM",
                 4: "FERRET_EDEVICE"}
@@ -103,6 +104,7 @@ SIGNATURES = {
     "ferret_plan_step_bytes": (c_int64, [_P]),
     "ferret_push_version": (c_int32, [_P, _P, _P, c_int32, _P, _P]),
     "ferret_compensate_step": (c_int32, [_P, _P, _P, _P, c_float, c_float, _P, _P, _P, _P]),
+    "ferret_compensate_step_noalloc": (c_int32, [_P, _P, _P, _P, c_float, c_float, _P, _P, _P]),
     "ferret_compensate_step_adaptive": (c_int32, [_P, _P, _P, _P, POINTER(ferret_adaptive), c_float, _P, _P, _P, _P]),
     "ferret_compensate_stages_adaptive": (c_int32, [_P, _P, _P, _P, POINTER(c_int32), POINTER(ferret_adaptive), c_float,
                                                     _P, _P, _P, _P]),
@@ -222,6 +224,12 @@ def ferret_compensate_step(plan: "Plan", ring, grads, master, lam: float, lr: fl
     _check(load().ferret_compensate_step(plan.handle, _ptr(ring), _ptr(grads), _ptr(master), lam, lr,
                                          _ptr(norms_out), _ptr(grad_out), _ptr(workspace),
                                          _stream(stream)))
+
+
+def ferret_compensate_step_noalloc(plan: "Plan", ring, grads, master, lam: float, lr: float, norms_out=None,
+                                   grad_out=None, stream=None) -> None:
+    _check(load().ferret_compensate_step_noalloc(plan.handle, _ptr(ring), _ptr(grads), _ptr(master), lam, lr,
+                                                 _ptr(norms_out), _ptr(grad_out), _stream(stream)))
 
 
 def ferret_compensate_step_adaptive(plan: "Plan", ring, grads, master, lambda_dev, v_r, v_a, alpha: float,

@@ -434,6 +434,31 @@ ferret_status ferret_compensate_step(const ferret_plan *plan, void *ring, const 
     return FERRET_OK;
 }
 
+ferret_status ferret_compensate_step_noalloc(const ferret_plan *plan, void *ring, const void *grads, float *master,
+                                             float lambda, float lr, float *norms_out, void *grad_out,
+                                             void *hip_stream) {
+    const char *who = "compensate_step_noalloc";
+    if (plan && plan->n_chunks > FERRET_NOALLOC_MAX_CHUNKS) {
+        set_error("%s: the plan has %lld chunks, the library's own scratch holds partial sums for at most %d; "
+                  "plan with a larger chunk_elems or use ferret_compensate_step with a workspace", who,
+                  (long long)plan->n_chunks, FERRET_NOALLOC_MAX_CHUNKS);
+        return FERRET_EINVAL;
+    }
+    void *scratch_ptr = nullptr;
+    if (norms_out) {                    // the scratch is only touched when norms are asked for
+        int err = noalloc_scratch(&scratch_ptr);
+        if (err) { set_error("%s: looking up the scratch array failed: %s", who, device_error_string(err)); return FERRET_EDEVICE; }
+    }
+    ferret_status rc = check_step_args(who, plan, ring, grads, master, norms_out, grad_out, scratch_ptr);
+    if (rc != FERRET_OK) return rc;
+    StepArgs a;
+    fill_step_args(plan, a, ring, grads, master, lambda, lr, norms_out, grad_out, scratch_ptr);
+    int err = launch_step(*plan, a, norms_out, hip_stream);
+    if (err) { set_error("%s: launch failed: %s", who, device_error_string(err)); return FERRET_EDEVICE; }
+    for (const Stage &s : plan->stages) s.step_pending = true;
+    return FERRET_OK;
+}
+
 static ferret_status check_adaptive(const char *who, const ferret_plan *plan, const ferret_adaptive *ad,
                                     void *workspace) {
     if (!ad || !ad->lambda || !ad->v_r || !ad->v_a || !workspace) {

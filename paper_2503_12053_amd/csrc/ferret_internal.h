@@ -17,6 +17,9 @@
 
 namespace ferret {
 
+// Bytes of the library-owned scratch array behind ferret_compensate_step_noalloc: five per-chunk series.
+#define FERRET_NOALLOC_SCRATCH_BYTES ((size_t)FERRET_NOALLOC_MAX_CHUNKS * 5u * sizeof(float))
+
 // ---- what travels to the device as a kernel argument -------------------------------------
 // One entry per pipeline stage.  48 bytes; FERRET_MAX_STAGES of them stay under the 4 KiB
 // kernel-argument limit.  Every workgroup copies the live entries into LDS once and looks
@@ -138,6 +141,7 @@ int launch_read(const void *src, size_t n_bytes, void *sink, void *stream);
 int launch_mix(void *dst, const void *src, size_t src_stride_bytes, int n_reads, size_t n_bytes, int resident_cap,
                void *stream);
 const char *device_error_string(int err);
+int noalloc_scratch(void **ptr_out);                        // device address of the library's own scratch on the current device
 int profile_begin(int32_t capacity);                       // 0 ok, -1 bad state, >0 hipError_t
 int profile_end(float *ms_out, int32_t cap, int32_t *n_out);
 

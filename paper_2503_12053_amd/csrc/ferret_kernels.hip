@@ -27,6 +27,7 @@
 //   * no matrix cores: there is no contraction anywhere on this path.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
 #include <vector>
 
 #include "ferret_internal.h"
@@ -1280,6 +1281,32 @@ int launch_mix(void *dst, const void *src, size_t src_stride_bytes, int n_reads,
 }
 
 const char *device_error_string(int err) { return hipGetErrorString(static_cast<hipError_t>(err)); }
+
+// ---- library-owned scratch of the entry point that allocates nothing ---------------------------------
+// The per-chunk partial sums of ferret_compensate_step_noalloc live in this array instead of a caller's
+// workspace.  Every GPU the library runs on holds its own copy at its own address; in host code the
+// array's name is only a handle for hipGetSymbolAddress, never an address to pass to a kernel.
+static __device__ __align__(256) unsigned char scratch[FERRET_NOALLOC_SCRATCH_BYTES];
+static void *g_scratch_ptr[64];          // per device ordinal: device address of `scratch`, null = not looked up yet
+static std::mutex g_scratch_mutex;
+
+int noalloc_scratch(void **ptr_out) {
+    *ptr_out = nullptr;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return (int)e;
+    if (dev < 0 || dev >= 64) return (int)hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {           // once per device, with that device current
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return (int)e;
+        if (!p) return (int)hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr_out = g_scratch_ptr[dev];
+    return 0;
+}
 #endif  // FERRET_TU_COMMON
 
 }  // namespace ferret

@@ -228,6 +228,25 @@ def test_step_and_push_argument_errors(lib):
     assert lib.ferret_copy_bytes(16, 16, 0, None) == B.FERRET_OK
 
 
+def test_noalloc_step_rejects_plans_beyond_its_scratch(lib):
+    """The entry point that allocates nothing holds partial sums for a fixed number of chunks; a plan with more
+    is refused before any device call (so this runs without a GPU), with the same argument checks otherwise."""
+    fn = lib.ferret_compensate_step_noalloc
+    n = (B.FERRET_NOALLOC_MAX_CHUNKS + 1) * 1024
+    plan, _ = _plan([[n]], [0], R=1, chunk=1024)
+    plan.set_state([0], [1])
+    assert plan.n_chunks == B.FERRET_NOALLOC_MAX_CHUNKS + 1
+    assert fn(plan.handle, 16, 16, None, 0.5, 0.01, None, None, None) == B.FERRET_EINVAL
+    assert "chunks" in B.last_error() and str(B.FERRET_NOALLOC_MAX_CHUNKS) in B.last_error()
+    header = open(os.path.join(ROOT, "include", "ferret.h")).read()
+    assert re.search(r"#define\s+FERRET_NOALLOC_MAX_CHUNKS\s+%d\b" % B.FERRET_NOALLOC_MAX_CHUNKS, header)
+    small, _ = _plan([[64]], [1], R=2)
+    small.set_state([0], [1])
+    assert fn(None, 16, 16, None, 0.5, 0.01, None, None, None) == B.FERRET_EINVAL
+    assert fn(small.handle, 24, 16, None, 0.5, 0.01, None, None, None) == B.FERRET_EINVAL       # misaligned ring
+    assert fn(small.handle, 16, 16, 32, 0.5, 0.01, None, None, None) == B.FERRET_EINVAL         # master on fp32 plan
+
+
 def test_queries_on_null_or_out_of_range(lib):
     assert lib.ferret_plan_n_stages(None) == -1
     assert lib.ferret_plan_ring_bytes(None) == 0
