@@ -82,17 +82,31 @@ typedef struct {
     int64_t slot_align_elems;  /* slot stride is rounded up to a multiple of this (multiple of 64) */
     int64_t slot_skew_elems;   /* then this is added (multiple of 8): de-phases the streams that
                                   read the same element of different slots */
+    int64_t chunk_bytes;       /* only with chunk_elems = 0: every stage gets its own chunk size, the multiple of 1024
+                                  elements nearest to chunk_bytes / (bytes one parameter of that stage has in flight
+                                  in a step: gradient, the K'+1 versions -- 8 of them when K' > 8 --, new version,
+                                  master read and write), so that every workgroup moves about chunk_bytes whatever
+                                  the stage's K'; 0: 48 KiB for plans beyond 240 MiB, else 2048 elements throughout */
     int32_t blocks_per_cu;     /* >0: persistent grid of blocks_per_cu * (number of CUs) workgroups with
                                   the stage table staged in LDS; <0: one workgroup per chunk; 0: default */
-    int32_t resident_cap;      /* >0: at most this many workgroups resident per CU (enforced by reserving
-                                  LDS that the kernel does not use); <0: no cap; 0: default */
+    int32_t resident_cap;      /* >=2: at most this many workgroups resident per CU (enforced by reserving
+                                  LDS that the kernel does not use; one workgroup can hold at most 64 KiB of a
+                                  CU's 160 KiB, so 1 is not available); <0: no cap; 0: default */
     int32_t newest_from_master; /* FERRET_BF16_MASTER_F32 only.  1: the caller promises that in every stage the
                                   newest stored version equals the round-to-nearest-even bf16 of the master
                                   (always true when both come from ferret_push_version with a master and
-                                  ferret_compensate_step); the step then recomputes V[tau] from the master
-                                  instead of reading it (2 bytes per parameter less).  If the promise is
-                                  broken the drifts are taken against the wrong newest version.  0: read it. */
-    int32_t reserved;          /* must be 0 */
+                                  ferret_compensate_step); ferret_compensate_step, _noalloc and
+                                  ferret_compensate_stages then recompute V[tau] from the master instead of
+                                  reading it (2 bytes per parameter less).  If the promise is broken the drifts
+                                  are taken against the wrong newest version.  The adaptive, accumulating and
+                                  penalised steps always read V[tau] (same results, no saving); not available
+                                  together with blocks_per_cu > 0.  0: read it. */
+    int32_t cache_policy;      /* 0: plans whose ring, gradient and master together stay below 240 MiB (they
+                                  remain in the 256 MB memory-side cache from step to step) run the plain step
+                                  with ordinary cached accesses, everything else with non-temporal ones;
+                                  1: cached wherever that variant exists; 2: always non-temporal.  Results are
+                                  bit-identical either way. */
+    int32_t reserved[2];       /* must be 0 */
 } ferret_tuning;
 
 typedef struct ferret_plan ferret_plan;   /* opaque; host memory; owned by the caller via destroy */
@@ -108,7 +122,10 @@ typedef struct ferret_plan ferret_plan;   /* opaque; host memory; owned by the c
  *                       maximum staleness of stage j in a P-stage pipeline is P-1-j
  *   n_iters             K >= 0, or FERRET_ITERS_FULL
  *   ring_depth          R >= 1 versions kept per stage, or FERRET_RING_DEPTH_MINIMAL
- *   chunk_elems         0 = default (2048); otherwise a multiple of 1024, at most 2^24
+ *   chunk_elems         0 = default: 2048 for plans whose ring, gradient and master together stay below 240 MiB
+ *                       (they live in the memory-side cache); for larger plans per stage, about 48 KiB of traffic
+ *                       per chunk (fp32: 2048 elements at K' = 3, 3072 at K' = 1, 1024 at K' >= 6; see
+ *                       tuning->chunk_bytes); otherwise a multiple of 1024, at most 2^24, used for every stage
  *   tuning              NULL or options
  *   out_plan            receives the plan; heads start at slot 0 with no valid version
  */
@@ -129,8 +146,8 @@ int32_t ferret_plan_n_stages(const ferret_plan *plan);
 int32_t ferret_plan_n_tensors(const ferret_plan *plan);
 int32_t ferret_plan_precision(const ferret_plan *plan);
 int32_t ferret_plan_n_iters(const ferret_plan *plan);
-int64_t ferret_plan_chunk_elems(const ferret_plan *plan);
-int64_t ferret_plan_n_chunks(const ferret_plan *plan);
+int64_t ferret_plan_chunk_elems(const ferret_plan *plan);     /* the largest chunk size of any stage */
+int64_t ferret_plan_n_chunks(const ferret_plan *plan);        /* over all stages */
 int64_t ferret_plan_flat_elems(const ferret_plan *plan);      /* elements of a slot-shaped buffer */
 int64_t ferret_plan_ring_elems(const ferret_plan *plan);      /* elements of the whole ring */
 size_t ferret_plan_ring_bytes(const ferret_plan *plan);
@@ -147,6 +164,8 @@ int64_t ferret_plan_stage_ring_offset(const ferret_plan *plan, int32_t stage);
 int64_t ferret_plan_stage_slot_stride(const ferret_plan *plan, int32_t stage);
 int32_t ferret_plan_stage_ring_depth(const ferret_plan *plan, int32_t stage);
 int32_t ferret_plan_stage_staleness(const ferret_plan *plan, int32_t stage);   /* configured tau_j */
+int64_t ferret_plan_stage_chunk_elems(const ferret_plan *plan, int32_t stage); /* elements per chunk of this stage */
+int64_t ferret_plan_stage_n_chunks(const ferret_plan *plan, int32_t stage);
 int64_t ferret_plan_tensor_offset(const ferret_plan *plan, int32_t tensor);    /* inside its stage */
 
 /* ---- ring state (host integers only) --------------------------------------------------------- */
@@ -180,6 +199,8 @@ int64_t ferret_plan_step_bytes(const ferret_plan *plan);
  *            src == NULL: commit only -- advance head and count the version that the preceding
  *              ferret_compensate_step wrote into that slot.  FERRET_ESTATE if no step has been
  *              issued for the stage since its last commit.
+ *              A push with src != NULL while a step of the stage is still uncommitted goes to the same slot
+ *              the step wrote, i.e. it replaces that step's version (the step is dropped, not committed).
  * The host state changes when the call returns; the copy itself is ordered on hip_stream.
  */
 ferret_status ferret_push_version(ferret_plan *plan, void *ring, float *master, int32_t stage,
@@ -202,7 +223,9 @@ ferret_status ferret_push_version(ferret_plan *plan, void *ring, float *master, 
  *              sum (V[tau]-V[0])^2 (deterministic: per-chunk partials summed in chunk order)
  *   grad_out   device fp32 flat buffer or NULL: the compensated gradient g_K' (for checks and
  *              for optimisers that want it)
- *   workspace  device, workspace_bytes; required iff norms_out != NULL; contents undefined after
+ *   workspace  device, workspace_bytes; required iff norms_out != NULL; needs no initialisation, contents
+ *              undefined after.  One workspace serves one call at a time: calls that may overlap (different
+ *              streams) need separate workspaces.
  * FERRET_ESTATE if some stage holds no version yet.
  */
 ferret_status ferret_compensate_step(const ferret_plan *plan, void *ring, const void *grads,
@@ -346,7 +369,7 @@ ferret_status ferret_penalized_step(const ferret_plan *plan, void *ring, const v
 
 /* ---- misc ------------------------------------------------------------------------------------ */
 const char *ferret_last_error(void);   /* message of the calling thread's last failed call */
-const char *ferret_version(void);
+const char *ferret_version(void);      /* "libferret <version> (gfx950) src <hash>": hash of the sources it was built from */
 
 /* Plain device-to-device copy through the library's own copy kernel (n_bytes multiple of 16,
  * 16-byte aligned pointers).  Measures the streaming ceiling of the machine with the same

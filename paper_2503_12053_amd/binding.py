@@ -38,9 +38,9 @@ class ferret_tensor(ctypes.Structure):
 
 
 class ferret_tuning(ctypes.Structure):
-    _fields_ = [("slot_align_elems", c_int64), ("slot_skew_elems", c_int64),
+    _fields_ = [("slot_align_elems", c_int64), ("slot_skew_elems", c_int64), ("chunk_bytes", c_int64),
                 ("blocks_per_cu", c_int32), ("resident_cap", c_int32), ("newest_from_master", c_int32),
-                ("reserved", c_int32)]
+                ("cache_policy", c_int32), ("reserved", c_int32 * 2)]
 
 
 class ferret_adaptive(ctypes.Structure):
@@ -94,6 +94,8 @@ SIGNATURES = {
     "ferret_plan_stage_slot_stride": (c_int64, [_P, c_int32]),
     "ferret_plan_stage_ring_depth": (c_int32, [_P, c_int32]),
     "ferret_plan_stage_staleness": (c_int32, [_P, c_int32]),
+    "ferret_plan_stage_chunk_elems": (c_int64, [_P, c_int32]),
+    "ferret_plan_stage_n_chunks": (c_int64, [_P, c_int32]),
     "ferret_plan_tensor_offset": (c_int64, [_P, c_int32]),
     "ferret_plan_get_state": (c_int32, [_P, POINTER(c_int32), POINTER(c_int32)]),
     "ferret_plan_set_state": (c_int32, [_P, POINTER(c_int32), POINTER(c_int32)]),
@@ -205,9 +207,14 @@ def ferret_plan_buckets(tensors: Sequence, n_stages: int, staleness: Sequence[in
         rc = lib.ferret_plan_buckets(arr, len(tensors), n_stages, st, n_iters, ring_depth, prec,
                                      chunk_elems, byref(out))
     else:
+        unknown = set(tuning) - {n for n, _ in ferret_tuning._fields_}
+        if unknown:
+            raise ValueError(f"unknown tuning fields {sorted(unknown)}")
         tn = ferret_tuning(int(tuning.get("slot_align_elems", 0)), int(tuning.get("slot_skew_elems", 0)),
+                           int(tuning.get("chunk_bytes", 0)),
                            int(tuning.get("blocks_per_cu", 0)), int(tuning.get("resident_cap", 0)),
-                           int(tuning.get("newest_from_master", 0)), int(tuning.get("reserved", 0)))
+                           int(tuning.get("newest_from_master", 0)), int(tuning.get("cache_policy", 0)),
+                           (c_int32 * 2)(int(tuning.get("reserved", 0)), 0))
         rc = lib.ferret_plan_buckets_tuned(arr, len(tensors), n_stages, st, n_iters, ring_depth, prec,
                                            chunk_elems, byref(tn), byref(out))
     _check(rc)
@@ -362,6 +369,8 @@ class Plan:
     def stage_slot_stride(self, j): return self._q("stage_slot_stride", j)
     def stage_ring_depth(self, j): return self._q("stage_ring_depth", j)
     def stage_staleness(self, j): return self._q("stage_staleness", j)
+    def stage_chunk_elems(self, j): return self._q("stage_chunk_elems", j)
+    def stage_n_chunks(self, j): return self._q("stage_n_chunks", j)
     def tensor_offset(self, i): return self._q("tensor_offset", i)
     def stage_effective_staleness(self, j): return self._q("stage_effective_staleness", j)
     def stage_effective_iters(self, j): return self._q("stage_effective_iters", j)

@@ -7,6 +7,7 @@ installed.  hipcc cross-compiles: no GPU is needed to build.
 """
 from __future__ import annotations
 
+import hashlib
 import os
 import shutil
 import subprocess
@@ -38,9 +39,22 @@ FLAGS = [f"--offload-arch={ARCH}", "-O3", "-std=c++17", "-fPIC",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 
+def source_hash() -> str:
+    """First 12 hex digits of the SHA-256 over every source and header the library is built from (in a fixed
+    order) and the compiler flags.  The library reports it through ferret_version(), so that a measurement can
+    say which sources it belongs to and a stored profile summary can be matched against the build that is timed."""
+    h = hashlib.sha256()
+    for path in sorted(SOURCES + HEADERS):
+        h.update(os.path.basename(path).encode() + b"\0")
+        with open(path, "rb") as f:
+            h.update(f.read())
+    h.update(" ".join(f for f in FLAGS if not f.startswith("/") and os.sep not in f).encode())
+    return h.hexdigest()[:12]
+
+
 def command(out: str = LIB) -> list:
     """The whole library as ONE hipcc command (every source one translation unit each)."""
-    return [hipcc(), *FLAGS, "-shared", "-x", "hip", *SOURCES, "-o", out]
+    return [hipcc(), *FLAGS, f'-DFERRET_SOURCE_HASH="{source_hash()}"', "-shared", "-x", "hip", *SOURCES, "-o", out]
 
 
 def compile_jobs(objdir: str) -> list:
@@ -55,7 +69,7 @@ def compile_jobs(objdir: str) -> list:
     for src in SOURCES:
         if src != kernels:
             obj = os.path.join(objdir, os.path.basename(src) + ".o")
-            jobs.append(([hipcc(), *FLAGS, "-c", "-x", "hip", src, "-o", obj], obj))
+            jobs.append(([hipcc(), *FLAGS, f'-DFERRET_SOURCE_HASH="{source_hash()}"', "-c", "-x", "hip", src, "-o", obj], obj))
     return jobs
 
 

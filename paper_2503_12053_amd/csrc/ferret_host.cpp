@@ -50,6 +50,7 @@ static void fill_step_descs(const ferret_plan &p, StageDesc *out) {
         d.flat_off = (uint64_t)s.flat_off;
         d.n_elems = (uint64_t)s.n_elems;
         d.chunk_begin = (uint32_t)s.chunk_begin;
+        d.chunk_elems = (uint32_t)s.chunk_elems;
         d.ring_depth = (uint16_t)s.ring_depth;
         d.head = (uint16_t)s.head;
         int32_t tau = effective_tau(s);
@@ -65,7 +66,10 @@ using namespace ferret;
 extern "C" {
 
 const char *ferret_last_error(void) { return g_err; }
-const char *ferret_version(void) { return "libferret 0.1 (gfx950)"; }
+#ifndef FERRET_SOURCE_HASH
+#define FERRET_SOURCE_HASH "unknown"
+#endif
+const char *ferret_version(void) { return "libferret 0.2 (gfx950) src " FERRET_SOURCE_HASH; }
 
 ferret_status ferret_plan_buckets(const ferret_tensor *tensors, int32_t n_tensors, int32_t n_stages,
                                   const int32_t *staleness, int32_t n_iters, int32_t ring_depth,
@@ -95,18 +99,25 @@ ferret_status ferret_plan_buckets_tuned(const ferret_tensor *tensors, int32_t n_
     }
     const int64_t vec = vec_elems(prec);
     const int64_t chunk_unit = kThreads * vec;                 // one vector per thread
-    // default (measured best on MI355X together with the resident-workgroup cap): two vectors per lane,
-    // i.e. 2048 elements per workgroup for both storage types
-    if (chunk_elems == 0) chunk_elems = 2 * chunk_unit;
-    if (chunk_elems < 0 || chunk_elems % chunk_unit != 0 || chunk_elems > (int64_t(1) << 24)) {   // lanes address a chunk with 32-bit byte offsets
-        set_error("plan: chunk_elems = %lld, need a positive multiple of %lld up to 2^24", (long long)chunk_elems,
+    constexpr int64_t kMaxChunkElems = int64_t(1) << 24;      // lanes address a chunk with 32-bit byte offsets
+    if (chunk_elems < 0 || chunk_elems % chunk_unit != 0 || chunk_elems > kMaxChunkElems) {
+        set_error("plan: chunk_elems = %lld, need 0 or a positive multiple of %lld up to 2^24", (long long)chunk_elems,
                   (long long)chunk_unit);
         return FERRET_EINVAL;
     }
-    int64_t slot_align = kDefaultSlotAlign, slot_skew = 0;
-    int32_t blocks_per_cu = 0, resident_cap = 0, newest_from_master = 0;
+    int64_t slot_align = kDefaultSlotAlign, slot_skew = 0, chunk_bytes = 0;
+    int32_t blocks_per_cu = 0, resident_cap = 0, newest_from_master = 0, cache_policy = 0;
     if (tuning) {
-        if (tuning->reserved != 0) { set_error("plan: tuning.reserved must be 0"); return FERRET_EINVAL; }
+        if (tuning->reserved[0] != 0 || tuning->reserved[1] != 0) { set_error("plan: tuning.reserved must be 0"); return FERRET_EINVAL; }
+        chunk_bytes = tuning->chunk_bytes;
+        if (chunk_bytes < 0 || chunk_bytes > (int64_t(1) << 30)) {
+            set_error("plan: chunk_bytes = %lld, need 0 .. 2^30", (long long)chunk_bytes); return FERRET_EINVAL;
+        }
+        if (chunk_bytes > 0 && chunk_elems > 0) {
+            set_error("plan: give chunk_elems or tuning.chunk_bytes, not both"); return FERRET_EINVAL;
+        }
+        cache_policy = tuning->cache_policy;
+        if (cache_policy < 0 || cache_policy > 2) { set_error("plan: cache_policy = %d, need 0..2", cache_policy); return FERRET_EINVAL; }
         newest_from_master = tuning->newest_from_master;
         if (newest_from_master != 0 && newest_from_master != 1) {
             set_error("plan: newest_from_master = %d, need 0 or 1", newest_from_master); return FERRET_EINVAL;
@@ -115,7 +126,9 @@ ferret_status ferret_plan_buckets_tuned(const ferret_tensor *tensors, int32_t n_
             set_error("plan: newest_from_master only applies to FERRET_BF16_MASTER_F32"); return FERRET_EINVAL;
         }
         resident_cap = tuning->resident_cap;
-        if (resident_cap > 32) { set_error("plan: resident_cap = %d, need <= 32", resident_cap); return FERRET_EINVAL; }
+        if (resident_cap > 32 || resident_cap == 1) {      // one workgroup may reserve at most 64 KiB of the CU's 160 KiB of LDS
+            set_error("plan: resident_cap = %d, need 2..32, 0 (default) or < 0 (none)", resident_cap); return FERRET_EINVAL;
+        }
         if (tuning->slot_align_elems) slot_align = tuning->slot_align_elems;
         slot_skew = tuning->slot_skew_elems;
         blocks_per_cu = tuning->blocks_per_cu;
@@ -130,6 +143,9 @@ ferret_status ferret_plan_buckets_tuned(const ferret_tensor *tensors, int32_t n_
             return FERRET_EINVAL;
         }
         if (blocks_per_cu > 64) { set_error("plan: blocks_per_cu = %d, need <= 64", blocks_per_cu); return FERRET_EINVAL; }
+        if (newest_from_master && blocks_per_cu > 0) {
+            set_error("plan: newest_from_master is not available with a persistent grid (blocks_per_cu > 0)"); return FERRET_EINVAL;
+        }
     }
     for (int32_t j = 0; j < n_stages; ++j) {
         if (staleness[j] < 0) { set_error("plan: staleness[%d] = %d < 0", j, staleness[j]); return FERRET_EINVAL; }
@@ -155,6 +171,7 @@ ferret_status ferret_plan_buckets_tuned(const ferret_tensor *tensors, int32_t n_
     p->prec = prec;
     p->n_iters = n_iters;
     p->chunk_elems = chunk_elems;
+    p->cache_policy = cache_policy;
     p->blocks_per_cu = blocks_per_cu;
     p->resident_cap = resident_cap;
     p->newest_from_master = newest_from_master;
@@ -186,7 +203,7 @@ ferret_status ferret_plan_buckets_tuned(const ferret_tensor *tensors, int32_t n_
         delete p; return FERRET_EINVAL;
     }
 
-    // layout + chunks
+    // layout
     int64_t flat = 0, ring = 0, chunks = 0;
     for (int32_t j = 0; j < n_stages; ++j) {
         Stage &s = p->stages[j];
@@ -197,8 +214,29 @@ ferret_status ferret_plan_buckets_tuned(const ferret_tensor *tensors, int32_t n_
         s.slot_stride = round_up(s.n_elems, slot_align) + slot_skew;
         s.ring_base = ring;
         ring += round_up(s.slot_stride * s.ring_depth, kStageAlign);
+    }
+    // chunks.  Size per stage: the caller's; else, for plans that stream (working set beyond the memory-side
+    // cache), the multiple of one-vector-per-lane nearest to chunk_bytes of traffic in flight per chunk, so that
+    // every workgroup moves about the same bytes whatever its stage's K' and one resident-workgroup cap suits
+    // every stage of a launch; else two vectors per lane for every stage.
+    const bool by_bytes = chunk_elems == 0 && (chunk_bytes > 0 || working_set_bytes(prec, ring, flat) > kCacheResidentBytes);
+    // default byte target, measured on MI355X together with the resident-workgroup cap: 48 KiB, i.e. 2048
+    // elements at K' = 3 in fp32, more for stages that read fewer versions, fewer for deeper ones
+    if (by_bytes && chunk_bytes == 0) chunk_bytes = 48 * 1024;
+    p->chunk_bytes = by_bytes ? chunk_bytes : 0;
+    for (int32_t j = 0; j < n_stages; ++j) {
+        Stage &s = p->stages[j];
+        s.chunk_elems = chunk_elems > 0 ? chunk_elems : 2 * chunk_unit;
+        if (by_bytes) {
+            const int32_t kp = effective_iters(n_iters, staleness[j]);
+            // a stage that iterates nothing still reads V[0] when the weight gap is wanted (norms, gap penalty)
+            const int64_t per = inflight_bytes_per_elem(prec, kp) + (kp == 0 && staleness[j] > 0 ? storage_bytes(prec) : 0);
+            int64_t units = (chunk_bytes + per * chunk_unit / 2) / (per * chunk_unit);
+            if (units < 1) units = 1;
+            s.chunk_elems = units * chunk_unit > kMaxChunkElems ? kMaxChunkElems : units * chunk_unit;
+        }
         s.chunk_begin = chunks;
-        s.n_chunks = (s.n_elems + chunk_elems - 1) / chunk_elems;
+        s.n_chunks = (s.n_elems + s.chunk_elems - 1) / s.chunk_elems;
         chunks += s.n_chunks;
     }
     if (chunks > 0x7fffffffLL) { set_error("plan: %lld chunks, too many; raise chunk_elems", (long long)chunks); delete p; return FERRET_EINVAL; }
@@ -220,7 +258,12 @@ int32_t ferret_plan_n_stages(const ferret_plan *plan) { return plan ? (int32_t)p
 int32_t ferret_plan_n_tensors(const ferret_plan *plan) { return plan ? (int32_t)plan->tensor_offset.size() : -1; }
 int32_t ferret_plan_precision(const ferret_plan *plan) { return plan ? (int32_t)plan->prec : -1; }
 int32_t ferret_plan_n_iters(const ferret_plan *plan) { return plan ? plan->n_iters : 0; }
-int64_t ferret_plan_chunk_elems(const ferret_plan *plan) { return plan ? plan->chunk_elems : -1; }
+int64_t ferret_plan_chunk_elems(const ferret_plan *plan) {
+    if (!plan) return -1;
+    int64_t largest = 0;
+    for (const Stage &s : plan->stages) largest = s.chunk_elems > largest ? s.chunk_elems : largest;
+    return largest;
+}
 int64_t ferret_plan_n_chunks(const ferret_plan *plan) { return plan ? plan->n_chunks : -1; }
 int64_t ferret_plan_flat_elems(const ferret_plan *plan) { return plan ? plan->flat_elems : -1; }
 int64_t ferret_plan_ring_elems(const ferret_plan *plan) { return plan ? plan->ring_elems : -1; }
@@ -240,6 +283,8 @@ int64_t ferret_plan_stage_ring_offset(const ferret_plan *plan, int32_t stage) { 
 int64_t ferret_plan_stage_slot_stride(const ferret_plan *plan, int32_t stage) { STAGE_OR(-1); return s.slot_stride; }
 int32_t ferret_plan_stage_ring_depth(const ferret_plan *plan, int32_t stage) { STAGE_OR(-1); return s.ring_depth; }
 int32_t ferret_plan_stage_staleness(const ferret_plan *plan, int32_t stage) { STAGE_OR(-1); return s.tau; }
+int64_t ferret_plan_stage_chunk_elems(const ferret_plan *plan, int32_t stage) { STAGE_OR(-1); return s.chunk_elems; }
+int64_t ferret_plan_stage_n_chunks(const ferret_plan *plan, int32_t stage) { STAGE_OR(-1); return s.n_chunks; }
 int64_t ferret_plan_tensor_offset(const ferret_plan *plan, int32_t tensor) {
     if (!plan || tensor < 0 || tensor >= (int32_t)plan->tensor_offset.size()) return -1;
     return plan->tensor_offset[tensor];
@@ -346,7 +391,6 @@ ferret_status ferret_push_version(ferret_plan *plan, void *ring, float *master, 
     a.ring = ring;
     a.master = master;
     a.src = static_cast<const float *>(src);
-    a.chunk_elems = (uint32_t)plan->chunk_elems;
     uint32_t chunks = 0, n = 0;
     for (int32_t j = j0; j < j1; ++j, ++n) {
         const Stage &s = plan->stages[j];
@@ -356,6 +400,7 @@ ferret_status ferret_push_version(ferret_plan *plan, void *ring, float *master, 
         d.flat_off = (uint64_t)s.flat_off;
         d.n_elems = (uint64_t)s.n_elems;
         d.chunk_begin = chunks;
+        d.chunk_elems = (uint32_t)s.chunk_elems;
         d.ring_depth = (uint16_t)s.ring_depth;
         d.head = (uint16_t)(s.valid == 0 ? s.head : (s.head + 1) % s.ring_depth);   // slot written
         chunks += (uint32_t)s.n_chunks;
@@ -369,8 +414,10 @@ ferret_status ferret_push_version(ferret_plan *plan, void *ring, float *master, 
 }
 
 // ---- step --------------------------------------------------------------------------------------
+// takes_part: null = every stage, else per stage non-zero = the stage is read and written by this call
 static ferret_status check_step_args(const char *who, const ferret_plan *plan, void *ring, const void *grads,
-                                     float *master, float *norms_out, void *grad_out, void *workspace) {
+                                     float *master, float *norms_out, void *grad_out, void *workspace,
+                                     const int32_t *takes_part) {
     if (!plan || !ring || !grads) { set_error("%s: null plan, ring or grads", who); return FERRET_EINVAL; }
     const bool mixed = plan->prec == FERRET_BF16_MASTER_F32;
     if (mixed && !master) { set_error("%s: bf16 plan needs the fp32 master", who); return FERRET_EINVAL; }
@@ -381,12 +428,19 @@ static ferret_status check_step_args(const char *who, const ferret_plan *plan, v
         set_error("%s: device pointers must be 16-byte aligned", who); return FERRET_EINVAL;
     }
     for (size_t j = 0; j < plan->stages.size(); ++j)
-        if (plan->stages[j].valid < 1) {
+        if ((!takes_part || takes_part[j] != 0) && plan->stages[j].valid < 1) {
             set_error("%s: stage %zu holds no weight version yet (push one first)", who, j);
             return FERRET_ESTATE;
         }
     return FERRET_OK;
 }
+static ferret_status check_step_args(const char *who, const ferret_plan *plan, void *ring, const void *grads,
+                                     float *master, float *norms_out, void *grad_out, void *workspace) {
+    return check_step_args(who, plan, ring, grads, master, norms_out, grad_out, workspace, nullptr);
+}
+
+// The step's scratch: five per-chunk series.
+static void use_workspace(StepArgs &a, void *workspace) { a.partials = static_cast<float *>(workspace); }
 
 static void fill_step_args(const ferret_plan *plan, StepArgs &a, void *ring, const void *grads, float *master,
                            float lambda, float lr, float *norms_out, void *grad_out, void *workspace) {
@@ -395,12 +449,12 @@ static void fill_step_args(const ferret_plan *plan, StepArgs &a, void *ring, con
     a.grads = grads;
     a.master = master;
     a.grad_out = static_cast<float *>(grad_out);
-    a.partials = norms_out ? static_cast<float *>(workspace) : nullptr;
+    a.norms_out = norms_out;
+    if (norms_out) use_workspace(a, workspace);
     a.lambda = lambda;
     a.lr = lr;
     a.n_stages = (uint32_t)plan->stages.size();
     a.n_chunks = (uint32_t)plan->n_chunks;
-    a.chunk_elems = (uint32_t)plan->chunk_elems;
     a.chunk_base = 0;
     a.chunk_end = a.n_chunks;
     fill_step_descs(*plan, a.stage);
@@ -427,7 +481,7 @@ ferret_status ferret_compensate_step(const ferret_plan *plan, void *ring, const 
     if (rc != FERRET_OK) return rc;
     StepArgs a;
     fill_step_args(plan, a, ring, grads, master, lambda, lr, norms_out, grad_out, workspace);
-    int err = launch_step(*plan, a, norms_out, hip_stream);
+    int err = launch_step(*plan, a, hip_stream);
     if (err) { set_error("compensate_step: launch failed: %s", device_error_string(err)); return FERRET_EDEVICE; }
     // bookkeeping only: remembers that slot head+1 now holds an uncommitted version
     for (const Stage &s : plan->stages) s.step_pending = true;
@@ -453,7 +507,7 @@ ferret_status ferret_compensate_step_noalloc(const ferret_plan *plan, void *ring
     if (rc != FERRET_OK) return rc;
     StepArgs a;
     fill_step_args(plan, a, ring, grads, master, lambda, lr, norms_out, grad_out, scratch_ptr);
-    int err = launch_step(*plan, a, norms_out, hip_stream);
+    int err = launch_step(*plan, a, hip_stream);
     if (err) { set_error("%s: launch failed: %s", who, device_error_string(err)); return FERRET_EDEVICE; }
     for (const Stage &s : plan->stages) s.step_pending = true;
     return FERRET_OK;
@@ -491,16 +545,16 @@ ferret_status ferret_compensate_stages(const ferret_plan *plan, void *ring, cons
                                        const int32_t *active, float lambda, float lr, float *norms_out,
                                        void *grad_out, void *workspace, void *hip_stream) {
     const char *who = "compensate_stages";
-    ferret_status rc = check_step_args(who, plan, ring, grads, master, norms_out, grad_out, workspace);
-    if (rc != FERRET_OK) return rc;
     if (!active) { set_error("%s: null active", who); return FERRET_EINVAL; }
+    ferret_status rc = check_step_args(who, plan, ring, grads, master, norms_out, grad_out, workspace, active);
+    if (rc != FERRET_OK) return rc;
     StepArgs a;
     fill_step_args(plan, a, ring, grads, master, lambda, lr, norms_out, grad_out, workspace);
     a.masked = 1;
     const size_t P = plan->stages.size();
     for (size_t j = 0; j < P; ++j) a.mode[j] = active[j] ? 2 : 0;
     narrow_chunk_span(plan, a);
-    int err = launch_step(*plan, a, norms_out, hip_stream);
+    int err = launch_step(*plan, a, hip_stream);
     if (err) { set_error("%s: launch failed: %s", who, device_error_string(err)); return FERRET_EDEVICE; }
     for (size_t j = 0; j < P; ++j)
         if (active[j]) plan->stages[j].step_pending = true;
@@ -510,7 +564,7 @@ ferret_status ferret_compensate_stages(const ferret_plan *plan, void *ring, cons
 static ferret_status adaptive_impl(const char *who, const ferret_plan *plan, void *ring, const void *grads,
                                    float *master, const int32_t *active, const ferret_adaptive *ad, float lr,
                                    float *norms_out, void *grad_out, void *workspace, void *hip_stream) {
-    ferret_status rc = check_step_args(who, plan, ring, grads, master, norms_out, grad_out, workspace);
+    ferret_status rc = check_step_args(who, plan, ring, grads, master, norms_out, grad_out, workspace, active);
     if (rc != FERRET_OK) return rc;
     rc = check_adaptive(who, plan, ad, workspace);
     if (rc != FERRET_OK) return rc;
@@ -525,14 +579,13 @@ static ferret_status adaptive_impl(const char *who, const ferret_plan *plan, voi
     int err = 0;
     if (ad->eta_lambda > 0.f && ad->fused) {
         a.fused_lambda = 1;                                // one pass: the step kernel runs the lambda block too
-        a.partials = static_cast<float *>(workspace);
+        use_workspace(a, workspace);
     } else if (ad->eta_lambda > 0.f) {
-        float *step_partials = a.partials;
-        a.partials = static_cast<float *>(workspace);
-        err = launch_lambda_update(*plan, a, hip_stream);
-        a.partials = step_partials;
+        StepArgs state = a;                                // the state pass always goes through the workspace
+        use_workspace(state, workspace);
+        err = launch_lambda_update(*plan, state, hip_stream);
     }
-    if (!err) err = launch_step(*plan, a, norms_out, hip_stream);
+    if (!err) err = launch_step(*plan, a, hip_stream);
     if (err) { set_error("%s: launch failed: %s", who, device_error_string(err)); return FERRET_EDEVICE; }
     for (size_t j = 0; j < plan->stages.size(); ++j)
         if (!active || active[j]) plan->stages[j].step_pending = true;
@@ -560,13 +613,13 @@ static ferret_status accumulate_impl(const char *who, const ferret_plan *plan, v
                                      float *master, const ferret_accumulate *acc, const ferret_adaptive *ad,
                                      float lambda, float lr, float *norms_out, void *grad_out, void *workspace,
                                      void *hip_stream) {
-    ferret_status rc = check_step_args(who, plan, ring, grads, master, norms_out, grad_out, workspace);
+    if (!acc || !acc->accum || !acc->mode) { set_error("%s: null accumulate, accum or mode", who); return FERRET_EINVAL; }
+    ferret_status rc = check_step_args(who, plan, ring, grads, master, norms_out, grad_out, workspace, plan ? acc->mode : nullptr);
     if (rc != FERRET_OK) return rc;
     if (ad) {
         rc = check_adaptive(who, plan, ad, workspace);
         if (rc != FERRET_OK) return rc;
     }
-    if (!acc || !acc->accum || !acc->mode) { set_error("%s: null accumulate, accum or mode", who); return FERRET_EINVAL; }
     if (!aligned16(acc->accum)) { set_error("%s: accum must be 16-byte aligned", who); return FERRET_EINVAL; }
     const size_t P = plan->stages.size();
     for (size_t j = 0; j < P; ++j) {
@@ -596,15 +649,14 @@ static ferret_status accumulate_impl(const char *who, const ferret_plan *plan, v
         set_adaptive_args(a, ad);
         if (ad->eta_lambda > 0.f && ad->fused) {
             a.fused_lambda = 1;          // one pass: the accumulation kernel runs the lambda block too
-            a.partials = static_cast<float *>(workspace);
+            use_workspace(a, workspace);
         } else if (ad->eta_lambda > 0.f) {      // lambda block of every participating stage, on this arrival's staleness
-            float *step_partials = a.partials;
-            a.partials = static_cast<float *>(workspace);
-            err = launch_lambda_update(*plan, a, hip_stream);
-            a.partials = step_partials;
+            StepArgs state = a;
+            use_workspace(state, workspace);
+            err = launch_lambda_update(*plan, state, hip_stream);
         }
     }
-    if (!err) err = launch_step(*plan, a, norms_out, hip_stream);
+    if (!err) err = launch_step(*plan, a, hip_stream);
     if (err) { set_error("%s: launch failed: %s", who, device_error_string(err)); return FERRET_EDEVICE; }
     for (size_t j = 0; j < P; ++j)
         if (acc->mode[j] == 2) plan->stages[j].step_pending = true;
@@ -647,7 +699,7 @@ ferret_status ferret_penalized_step(const ferret_plan *plan, void *ring, const v
         a.pen_scale[j] = scale ? scale[j] : 1.0f / (float)(tau > 1 ? tau : 1);
         a.pen_inv_c[j] = inv_c ? inv_c[j] : 0.f;
     }
-    int err = launch_step(*plan, a, norms_out, hip_stream);
+    int err = launch_step(*plan, a, hip_stream);
     if (err) { set_error("%s: launch failed: %s", who, device_error_string(err)); return FERRET_EDEVICE; }
     for (const Stage &s : plan->stages) s.step_pending = true;
     return FERRET_OK;

@@ -55,13 +55,9 @@ constexpr int kWaves = kThreads / 64;
 #ifndef FERRET_UNROLL
 #define FERRET_UNROLL 1
 #endif
-#ifndef FERRET_NT
-#define FERRET_NT 3                 // bit 0: non-temporal loads, bit 1: non-temporal stores
-#endif
 constexpr int kUnroll = FERRET_UNROLL;   // vectors per lane per stream loaded together when a chunk spans several groups
 [[maybe_unused]] constexpr int kUnrolledItersSmall = 4;    // LEVEL 0 kernels: every stage has K' <= 4
-[[maybe_unused]] constexpr int kUnrolledItersMid = 8;      // LEVEL 1 kernels: K' <= 8; LEVEL 2 adds the streamed path for any K'
-constexpr int kStreamBatch = 8;           // boundaries the streamed path loads together
+[[maybe_unused]] constexpr int kUnrolledItersMid = kUnrolledItersMax;   // LEVEL 1 kernels: K' <= 8; LEVEL 2 adds the streamed path (batches of kStreamBatch boundaries) for any K'
 [[maybe_unused]] constexpr uint64_t kCapThresholdBytes = 512ull << 20;
 
 // 16-byte vectors as clang vector types (so that the non-temporal builtins accept them)
@@ -70,21 +66,18 @@ typedef uint32_t v4u __attribute__((ext_vector_type(4)));
 typedef uint32_t v2u __attribute__((ext_vector_type(2)));
 
 // ---- small device helpers ---------------------------------------------------------------------
-template <typename T>
+// NT = true: non-temporal access (the data is not used again before it would be evicted anyway: steps that
+// stream far more than the caches hold); NT = false: ordinary cached access (steps whose whole working set
+// stays in the 256 MB memory-side cache from one step to the next).
+template <bool NT, typename T>
 __device__ __forceinline__ T ld(const T *p) {
-#if FERRET_NT & 1
-    return __builtin_nontemporal_load(p);
-#else
-    return *p;
-#endif
+    if constexpr (NT) return __builtin_nontemporal_load(p);
+    else return *p;
 }
-template <typename T>
+template <bool NT, typename T>
 __device__ __forceinline__ void st(T *p, const T &v) {
-#if FERRET_NT & 2
-    __builtin_nontemporal_store(v, p);
-#else
-    *p = v;
-#endif
+    if constexpr (NT) __builtin_nontemporal_store(v, p);
+    else *p = v;
 }
 __device__ __forceinline__ v4f make_v4f(float a, float b, float c, float d) {
     v4f r; r.x = a; r.y = b; r.z = c; r.w = d; return r;
@@ -112,19 +105,21 @@ __device__ __forceinline__ uint32_t bf16_pack(float lo, float hi) { return bf16_
 //   kElems      elements one lane handles per vector        kStoreBytes  bytes per stored element
 //   Raw         register type of one load of that vector    kRawBytes    bytes of that vector
 //   kMaster     the update goes to an fp32 master copy (kF4 = kElems/4 float4s per lane-vector)
-struct F32Store {
+template <bool NT_>
+struct F32StoreT {
     using Raw = v4f;
     static constexpr int kElems = 4, kStoreBytes = 4, kRawBytes = 16, kF4 = 1;
-    static constexpr bool kMaster = false;
+    static constexpr bool kMaster = false, kNT = NT_;
     __device__ static __forceinline__ void widen(const Raw &r, float (&x)[kElems]) {
         x[0] = r.x; x[1] = r.y; x[2] = r.z; x[3] = r.w;
     }
     __device__ static __forceinline__ Raw narrow(const float (&x)[kElems]) { return make_v4f(x[0], x[1], x[2], x[3]); }
 };
-struct Bf16Store8 {      // eight bf16 (16 bytes) per lane: widest loads, master as two float4 32 bytes apart
+template <bool NT_>
+struct Bf16Store8T {     // eight bf16 (16 bytes) per lane: widest loads, master as two float4 32 bytes apart
     using Raw = v4u;
     static constexpr int kElems = 8, kStoreBytes = 2, kRawBytes = 16, kF4 = 2;
-    static constexpr bool kMaster = true;
+    static constexpr bool kMaster = true, kNT = NT_;
     __device__ static __forceinline__ void widen(const Raw &r, float (&x)[kElems]) {
         x[0] = bf16_lo(r.x); x[1] = bf16_hi(r.x); x[2] = bf16_lo(r.y); x[3] = bf16_hi(r.y);
         x[4] = bf16_lo(r.z); x[5] = bf16_hi(r.z); x[6] = bf16_lo(r.w); x[7] = bf16_hi(r.w);
@@ -136,10 +131,11 @@ struct Bf16Store8 {      // eight bf16 (16 bytes) per lane: widest loads, master
         return o;
     }
 };
-struct Bf16Store4 {      // four bf16 (8 bytes) per lane: every access of a wavefront is one contiguous run
+template <bool NT_>
+struct Bf16Store4T {     // four bf16 (8 bytes) per lane: every access of a wavefront is one contiguous run
     using Raw = v2u;
     static constexpr int kElems = 4, kStoreBytes = 2, kRawBytes = 8, kF4 = 1;
-    static constexpr bool kMaster = true;
+    static constexpr bool kMaster = true, kNT = NT_;
     __device__ static __forceinline__ void widen(const Raw &r, float (&x)[kElems]) {
         x[0] = bf16_lo(r.x); x[1] = bf16_hi(r.x); x[2] = bf16_lo(r.y); x[3] = bf16_hi(r.y);
     }
@@ -150,10 +146,14 @@ struct Bf16Store4 {      // four bf16 (8 bytes) per lane: every access of a wave
     }
 };
 #if FERRET_BF16_LANE_ELEMS == 8
-using Bf16Store = Bf16Store8;
+template <bool NT_> using Bf16StoreT = Bf16Store8T<NT_>;
 #else
-using Bf16Store = Bf16Store4;
+template <bool NT_> using Bf16StoreT = Bf16Store4T<NT_>;
 #endif
+using F32Store = F32StoreT<true>;
+using Bf16Store = Bf16StoreT<true>;
+using F32StoreCached = F32StoreT<false>;
+using Bf16StoreCached = Bf16StoreT<false>;
 
 // Per-chunk partial sums a step can produce: series 0..2 are the three norms, series 3..4 the two inner
 // products of the "update lambda" block when that block is fused into the step (OUT & 16).
@@ -183,20 +183,20 @@ struct ChunkPtrs {
     float alpha;
 };
 
-template <typename T>
+template <bool NT, typename T>
 __device__ __forceinline__ T ld_off(const char *base, uint32_t byte_off) {
-    return ld(reinterpret_cast<const T *>(base + byte_off));
+    return ld<NT>(reinterpret_cast<const T *>(base + byte_off));
 }
-template <typename T>
+template <bool NT, typename T>
 __device__ __forceinline__ void st_off(char *base, uint32_t byte_off, const T &v) {
-    st(reinterpret_cast<T *>(base + byte_off), v);
+    st<NT>(reinterpret_cast<T *>(base + byte_off), v);
 }
 
 template <typename S>
 __device__ __forceinline__ void load_master(const char *master, uint32_t vec, v4f (&m)[S::kF4], bool needed = true) {
     if (S::kMaster && needed) {
 #pragma unroll
-        for (int q = 0; q < S::kF4; ++q) m[q] = ld_off<v4f>(master, vec * (uint32_t)(S::kElems * 4) + 16u * q);
+        for (int q = 0; q < S::kF4; ++q) m[q] = ld_off<S::kNT, v4f>(master, vec * (uint32_t)(S::kElems * 4) + 16u * q);
     }
 }
 
@@ -215,7 +215,7 @@ template <typename S, int OUT>
 __device__ __forceinline__ void load_accum(const char *accum, uint32_t vec, v4f (&ac)[S::kF4]) {
     if (OUT & 2) {
 #pragma unroll
-        for (int q = 0; q < S::kF4; ++q) ac[q] = ld_off<v4f>(accum, vec * (uint32_t)(S::kElems * 4) + 16u * q);
+        for (int q = 0; q < S::kF4; ++q) ac[q] = ld_off<S::kNT, v4f>(accum, vec * (uint32_t)(S::kElems * 4) + 16u * q);
     }
 }
 
@@ -234,7 +234,7 @@ __device__ __forceinline__ void update_and_store(const ChunkPtrs<NV> &p, uint32_
     if (OUT & 1) {
 #pragma unroll
         for (int q = 0; q < S::kF4; ++q)
-            st_off(p.g_out, vec * kF32Bytes + 16u * q, make_v4f(g[4 * q], g[4 * q + 1], g[4 * q + 2], g[4 * q + 3]));
+            st_off<S::kNT>(p.g_out, vec * kF32Bytes + 16u * q, make_v4f(g[4 * q], g[4 * q + 1], g[4 * q + 2], g[4 * q + 3]));
     }
     float step[E];          // what the update subtracts eta times: g, or scale * (running sum + g)
 #pragma unroll
@@ -248,12 +248,12 @@ __device__ __forceinline__ void update_and_store(const ChunkPtrs<NV> &p, uint32_
         if (!p.acc_update) {        // uniform: not the last arrival of the group, only the sum moves
 #pragma unroll
             for (int q = 0; q < S::kF4; ++q)
-                st_off(p.accum, vec * kF32Bytes + 16u * q,
+                st_off<S::kNT>(p.accum, vec * kF32Bytes + 16u * q,
                        make_v4f(step[4 * q], step[4 * q + 1], step[4 * q + 2], step[4 * q + 3]));
             return;
         }
 #pragma unroll
-        for (int q = 0; q < S::kF4; ++q) st_off(p.accum, vec * kF32Bytes + 16u * q, make_v4f(0.f, 0.f, 0.f, 0.f));
+        for (int q = 0; q < S::kF4; ++q) st_off<S::kNT>(p.accum, vec * kF32Bytes + 16u * q, make_v4f(0.f, 0.f, 0.f, 0.f));
 #pragma unroll
         for (int e = 0; e < E; ++e) step[e] *= p.acc_scale;
     }
@@ -263,13 +263,13 @@ __device__ __forceinline__ void update_and_store(const ChunkPtrs<NV> &p, uint32_
         for (int q = 0; q < S::kF4; ++q) {
             w[4 * q + 0] = fmaf(-lr, step[4 * q + 0], m_in[q].x); w[4 * q + 1] = fmaf(-lr, step[4 * q + 1], m_in[q].y);
             w[4 * q + 2] = fmaf(-lr, step[4 * q + 2], m_in[q].z); w[4 * q + 3] = fmaf(-lr, step[4 * q + 3], m_in[q].w);
-            st_off(p.master, vec * kF32Bytes + 16u * q, make_v4f(w[4 * q], w[4 * q + 1], w[4 * q + 2], w[4 * q + 3]));
+            st_off<S::kNT>(p.master, vec * kF32Bytes + 16u * q, make_v4f(w[4 * q], w[4 * q + 1], w[4 * q + 2], w[4 * q + 3]));
         }
     } else {
 #pragma unroll
         for (int e = 0; e < E; ++e) w[e] = fmaf(-lr, step[e], newest[e]);
     }
-    st_off(p.out, vec * (uint32_t)S::kRawBytes, S::narrow(w));
+    st_off<S::kNT>(p.out, vec * (uint32_t)S::kRawBytes, S::narrow(w));
 }
 
 // What the fused lambda block loads per lane-vector besides the step's own inputs.
@@ -282,11 +282,11 @@ struct LambdaIn {
 template <typename S, int OUT, int NV>
 __device__ __forceinline__ void load_lambda_in(const ChunkPtrs<NV> &p, uint32_t vec, LambdaIn<S> &in) {
     if (OUT & 16) {
-        in.v1 = ld_off<typename S::Raw>(p.v1, vec * (uint32_t)S::kRawBytes);
+        in.v1 = ld_off<S::kNT, typename S::Raw>(p.v1, vec * (uint32_t)S::kRawBytes);
 #pragma unroll
         for (int q = 0; q < S::kF4; ++q) {
-            in.vr[q] = ld_off<v4f>(p.v_r, vec * (uint32_t)(S::kElems * 4) + 16u * q);
-            in.va[q] = ld_off<v4f>(p.v_a, vec * (uint32_t)(S::kElems * 4) + 16u * q);
+            in.vr[q] = ld_off<S::kNT, v4f>(p.v_r, vec * (uint32_t)(S::kElems * 4) + 16u * q);
+            in.va[q] = ld_off<S::kNT, v4f>(p.v_a, vec * (uint32_t)(S::kElems * 4) + 16u * q);
         }
     }
 }
@@ -313,8 +313,8 @@ __device__ __forceinline__ void lambda_state_vector(const ChunkPtrs<NV> &p, uint
             r[i] = fmaf(alpha, r[i], beta * gi);
             s4[i] = fmaf(alpha, s4[i], beta * (gi * gi * (w1[4 * q + i] - w0[4 * q + i])));
         }
-        st_off(p.v_r, vec * FB + 16u * q, make_v4f(r[0], r[1], r[2], r[3]));
-        st_off(p.v_a, vec * FB + 16u * q, make_v4f(s4[0], s4[1], s4[2], s4[3]));
+        st_off<S::kNT>(p.v_r, vec * FB + 16u * q, make_v4f(r[0], r[1], r[2], r[3]));
+        st_off<S::kNT>(p.v_a, vec * FB + 16u * q, make_v4f(s4[0], s4[1], s4[2], s4[3]));
     }
 }
 
@@ -375,11 +375,11 @@ __device__ __forceinline__ void run_chunk(const ChunkPtrs<NV> &p, uint32_t n_vec
         v4f m[kUnroll][S::kF4], ac[kUnroll][S::kF4];
         LambdaIn<S> lin[kUnroll];
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) rg[u] = ld_off<Raw>(p.g, (base + u * kThreads + tid) * RB);
+        for (int u = 0; u < kUnroll; ++u) rg[u] = ld_off<S::kNT, Raw>(p.g, (base + u * kThreads + tid) * RB);
 #pragma unroll
         for (int s = 0; s < NV - ((OUT & 4) ? 1 : 0); ++s)
 #pragma unroll
-            for (int u = 0; u < kUnroll; ++u) rv[u][s] = ld_off<Raw>(p.v[s], (base + u * kThreads + tid) * RB);
+            for (int u = 0; u < kUnroll; ++u) rv[u][s] = ld_off<S::kNT, Raw>(p.v[s], (base + u * kThreads + tid) * RB);
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             load_master<S>(p.master, base + u * kThreads + tid, m[u], !(OUT & 2) || p.acc_update);
@@ -393,11 +393,11 @@ __device__ __forceinline__ void run_chunk(const ChunkPtrs<NV> &p, uint32_t n_vec
                                                    lambda, lr, acc);
     }
     for (uint32_t vec = n_grouped + tid; vec < n_vecs; vec += kThreads) {
-        Raw rg = ld_off<Raw>(p.g, vec * RB), rv[NV];
+        Raw rg = ld_off<S::kNT, Raw>(p.g, vec * RB), rv[NV];
         v4f m[S::kF4], ac[S::kF4];
         LambdaIn<S> lin;
 #pragma unroll
-        for (int s = 0; s < NV - ((OUT & 4) ? 1 : 0); ++s) rv[s] = ld_off<Raw>(p.v[s], vec * RB);
+        for (int s = 0; s < NV - ((OUT & 4) ? 1 : 0); ++s) rv[s] = ld_off<S::kNT, Raw>(p.v[s], vec * RB);
         load_master<S>(p.master, vec, m, !(OUT & 2) || p.acc_update);
         load_accum<S, OUT>(p.accum, vec, ac);
         load_lambda_in<S, OUT>(p, vec, lin);
@@ -419,8 +419,8 @@ __device__ __forceinline__ void run_chunk_streamed(const ChunkPtrs<1> &p, const 
     for (uint32_t vec = threadIdx.x; vec < n_vecs; vec += kThreads) {
         float g[E], prev[E], cur[E], first[E];
         v4f m[S::kF4], ac[S::kF4];
-        Raw rg = ld_off<Raw>(p.g, vec * RB);
-        Raw r0 = ld_off<Raw>(arena + (uint64_t)oldest * slot_bytes, vec * RB);      // kp >= 1 here: V[0] is not V[tau]
+        Raw rg = ld_off<S::kNT, Raw>(p.g, vec * RB);
+        Raw r0 = ld_off<S::kNT, Raw>(arena + (uint64_t)oldest * slot_bytes, vec * RB);      // kp >= 1 here: V[0] is not V[tau]
         load_master<S>(p.master, vec, m, !(OUT & 2) || p.acc_update);
         load_accum<S, OUT>(p.accum, vec, ac);
         LambdaIn<S> lin;
@@ -443,7 +443,7 @@ __device__ __forceinline__ void run_chunk_streamed(const ChunkPtrs<1> &p, const 
                 if ((uint32_t)b >= count) break;
                 const uint32_t s_i = (uint32_t)(((uint64_t)(i + b) * tau) / kp);
                 if ((OUT & 4) != 0 && S::kMaster && i + b == kp) r[b] = newest_from_master<S>(m);
-                else r[b] = ld_off<Raw>(arena + (uint64_t)((oldest + s_i) % R) * slot_bytes, vec * RB);
+                else r[b] = ld_off<S::kNT, Raw>(arena + (uint64_t)((oldest + s_i) % R) * slot_bytes, vec * RB);
             }
         };
         auto iterate_batch = [&](uint32_t i, const Raw (&r)[kStreamBatch]) {
@@ -489,6 +489,68 @@ __device__ __forceinline__ float wave_sum(float x) {
     return x;
 }
 
+// ---- ordered sums of per-chunk partials ------------------------------------------------------------
+// The library's one summation order for a stage's series of per-chunk partials, so that sums do not depend
+// on which kernel forms them or how the step was launched: 1024 "virtual lanes"; lane v adds the partials of
+// chunks c0+v, c0+v+1024, ... in that order in fp64; the 64 lanes of each of the 16 virtual wavefronts are
+// combined by an xor-shuffle tree; the 16 wavefront sums are added in wavefront order.  A workgroup of
+// THREADS < 1024 real lanes plays 1024/THREADS virtual lanes per real lane, v = t + THREADS*q: the same lane
+// position in virtual wavefront t/64 + (THREADS/64)*q, so every addition pairs the same operands.
+// Must be called by all THREADS lanes of the workgroup; total[] is valid in every lane afterwards.
+constexpr int kSumLanes = 1024;
+constexpr int kSumWaves = kSumLanes / 64;
+
+template <int NS, int THREADS>
+__device__ __forceinline__ void ordered_sums(const float *series0, size_t series_stride, uint32_t c0, uint32_t c1,
+                                             double (&red)[kSeries][kSumWaves], double (&total)[NS]) {
+    constexpr int Q = kSumLanes / THREADS, WAVES = THREADS / 64;
+    const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
+#pragma unroll 1
+    for (int q = 0; q < Q; ++q) {
+        double s[NS];
+#pragma unroll
+        for (int k = 0; k < NS; ++k) s[k] = 0.0;
+        uint32_t c = c0 + t + (uint32_t)(THREADS * q);
+        for (; c + 3u * kSumLanes < c1; c += 4u * kSumLanes) {          // four independent loads per series in flight
+            float x[NS][4];
+#pragma unroll
+            for (int k = 0; k < NS; ++k)
+#pragma unroll
+                for (int u = 0; u < 4; ++u) x[k][u] = series0[(size_t)k * series_stride + c + (uint32_t)(u * kSumLanes)];
+#pragma unroll
+            for (int k = 0; k < NS; ++k)
+#pragma unroll
+                for (int u = 0; u < 4; ++u) s[k] += (double)x[k][u];
+        }
+        for (; c < c1; c += kSumLanes)
+#pragma unroll
+            for (int k = 0; k < NS; ++k) s[k] += (double)series0[(size_t)k * series_stride + c];
+#pragma unroll
+        for (int k = 0; k < NS; ++k) {
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) s[k] += __shfl_xor(s[k], off, 64);
+            if (lane == 0) red[k][wave + WAVES * q] = s[k];
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < NS; ++k) {
+        double sum = 0.0;
+#pragma unroll
+        for (int w = 0; w < kSumWaves; ++w) sum += red[k][w];
+        total[k] = sum;
+    }
+}
+
+// Alg. 1, "update lambda": one gradient-descent step on || (1-alpha)(g_0 - v_r) - lambda v_a ||^2 given the two
+// inner products over the stage,  lambda <- lambda + 2 eta_lambda ((1-alpha) <v_a, g_0 - v_r> - lambda <v_a, v_a>).
+__device__ __forceinline__ float lambda_descent_step(float lambda_f, double dot_a_dr, double dot_a_a, float alpha,
+                                                     float eta_lambda) {
+    dot_a_dr *= (double)(1.0f - alpha);
+    const double lambda = (double)lambda_f;
+    return (float)(lambda + 2.0 * (double)eta_lambda * (dot_a_dr - lambda * dot_a_a));
+}
+
 // The wave-uniform facts about one chunk, taken from its stage's table entry.
 struct ChunkInfo {
     const char *arena;       // this chunk's first element in slot 0 of the stage's ring arena
@@ -506,9 +568,10 @@ __device__ __forceinline__ ChunkInfo chunk_info(const StepArgs &a, const StageDe
                                                 uint32_t stage) {
     constexpr uint64_t kStoreBytes = S::kStoreBytes;
     ChunkInfo c;
-    const uint64_t e0 = (uint64_t)(chunk - uniform(d.chunk_begin)) * a.chunk_elems;
+    const uint32_t chunk_elems = uniform(d.chunk_elems);
+    const uint64_t e0 = (uint64_t)(chunk - uniform(d.chunk_begin)) * chunk_elems;
     const uint64_t left = uniform(d.n_elems) - e0;
-    const uint32_t n_here = left < a.chunk_elems ? (uint32_t)left : a.chunk_elems;
+    const uint32_t n_here = left < chunk_elems ? (uint32_t)left : chunk_elems;
     c.n_vecs = n_here / S::kElems;
     c.R = uniform((uint32_t)d.ring_depth);
     c.head = uniform((uint32_t)d.head);
@@ -553,17 +616,18 @@ __device__ __forceinline__ void do_chunk(const StepArgs &a, const ChunkInfo &c, 
     run_chunk<S, NV, COMP, NORMS, OUT>(p, c.n_vecs, lambda, a.lr, acc);
 }
 
+// LDS of a step workgroup: cross-wavefront reduction of the chunk's partial sums.
+struct StepLds {
+    float red[kSeries][kWaves];
+};
+
 // One chunk, whatever its K': picks the unrolled variant (K' <= 4 or <= 8) or the streamed one, then
 // reduces the three partial sums of the workgroup and writes the chunk's partial.
 template <typename S, int LEVEL, bool NORMS, int OUT>
-__device__ __forceinline__ void process_chunk(const StepArgs &a, const ChunkInfo &c, uint32_t chunk,
-                                              float (&red)[kSeries][kWaves]) {
+__device__ __forceinline__ void process_chunk(const StepArgs &a, const ChunkInfo &c, uint32_t chunk, StepLds &lds) {
     float acc[kSeries] = {0.f, 0.f, 0.f, 0.f, 0.f};
     constexpr int PLAIN = OUT & ~16;      // a stage without staleness has no lambda block
-    if (c.skip) {       // uniform: this stage is not part of the call; its norms read as zero
-        if (NORMS && threadIdx.x < 3) a.partials[(size_t)threadIdx.x * a.n_chunks + chunk] = 0.f;
-        return;
-    }
+    if (c.skip) return;  // uniform: this stage is not part of the call (its norms are reported as zero elsewhere)
     // the coefficient: one scalar for the call, or this stage's self-tuned one from device memory
     // (read through the constant address space: a scalar load; the array was last written by an
     // earlier kernel of the same stream)
@@ -612,19 +676,19 @@ __device__ __forceinline__ void process_chunk(const StepArgs &a, const ChunkInfo
                                            lambda, a.lr, acc);
     }
     constexpr bool FUSED = (OUT & 16) != 0;
-    if (NORMS || FUSED) {
+    if constexpr (NORMS || FUSED) {
         constexpr int k0 = NORMS ? 0 : 3, k1 = FUSED ? kSeries : 3;      // the series this kernel produces
         const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
 #pragma unroll
         for (int k = k0; k < k1; ++k) {
             float s = wave_sum(acc[k]);
-            if (lane == 0) red[k][wave] = s;
+            if (lane == 0) lds.red[k][wave] = s;
         }
         __syncthreads();
         if (threadIdx.x >= (uint32_t)k0 && threadIdx.x < (uint32_t)k1) {
             float s = 0.f;
 #pragma unroll
-            for (int w = 0; w < kWaves; ++w) s += red[threadIdx.x][w];
+            for (int w = 0; w < kWaves; ++w) s += lds.red[threadIdx.x][w];
             a.partials[(size_t)threadIdx.x * a.n_chunks + chunk] = s;     // each series contiguous
         }
     }
@@ -640,7 +704,7 @@ __device__ __forceinline__ void process_chunk(const StepArgs &a, const ChunkInfo
 //                     need are not compiled in, which keeps the register footprint small.
 template <typename S, bool PERSISTENT, int LEVEL, bool NORMS, int OUT>
 __global__ void __launch_bounds__(kThreads) step_kernel(const StepArgs a) {
-    __shared__ float red[kSeries][kWaves];
+    __shared__ StepLds lds;
     if constexpr (PERSISTENT) {
         __shared__ StageDesc tab[FERRET_MAX_STAGES];
         {   // stage table: kernel-argument segment -> LDS, 12 dwords per stage
@@ -655,8 +719,8 @@ __global__ void __launch_bounds__(kThreads) step_kernel(const StepArgs a) {
             while (stage + 1 < a.n_stages && chunk >= tab[stage + 1].chunk_begin) ++stage;
             stage = uniform(stage);
             const ChunkInfo c = chunk_info<S>(a, tab[stage], chunk, stage);
-            process_chunk<S, LEVEL, NORMS, OUT>(a, c, chunk, red);
-            if (NORMS) __syncthreads();     // red[] is reused by the next chunk
+            process_chunk<S, LEVEL, NORMS, OUT>(a, c, chunk, lds);
+            if (NORMS) __syncthreads();     // lds.red is reused by the next chunk
         }
     } else {
         const uint32_t chunk = a.chunk_base + blockIdx.x;
@@ -670,7 +734,7 @@ __global__ void __launch_bounds__(kThreads) step_kernel(const StepArgs a) {
             for (uint32_t j = 16; j < FERRET_MAX_STAGES; ++j) stage += chunk >= a.chunk_begin[j] ? 1u : 0u;
         }
         const ChunkInfo c = chunk_info<S>(a, a.stage[stage], chunk, stage);
-        process_chunk<S, LEVEL, NORMS, OUT>(a, c, chunk, red);
+        process_chunk<S, LEVEL, NORMS, OUT>(a, c, chunk, lds);
     }
 }
 
@@ -679,12 +743,13 @@ __global__ void __launch_bounds__(kThreads) step_kernel(const StepArgs a) {
 // forms the chunk's share of <v_a, g_0 - v_r> and <v_a, v_a> on the OLD averages and writes the new
 // ones, v_r <- alpha v_r + (1-alpha) g_0 and v_a <- alpha v_a + (1-alpha) g_0 g_0 (V[1]-V[0]).
 // Reads g_0, V[0], V[1] (storage type) and v_r, v_a (fp32) once each: 28 bytes per fp32 parameter.
+// lambda_step_kernel sums the stage's two series afterwards and takes the lambda step.
 template <typename S>
 __global__ void __launch_bounds__(kThreads) lambda_state_kernel(const StepArgs a) {
     using Raw = typename S::Raw;
     constexpr int E = S::kElems;
     constexpr uint32_t RB = S::kRawBytes, FB = E * 4;
-    __shared__ float red[2][kWaves];
+    __shared__ StepLds lds;
     const uint32_t chunk = a.chunk_base + blockIdx.x;
     uint32_t stage = 0;
 #pragma unroll
@@ -694,8 +759,9 @@ __global__ void __launch_bounds__(kThreads) lambda_state_kernel(const StepArgs a
         for (uint32_t j = 16; j < FERRET_MAX_STAGES; ++j) stage += chunk >= a.chunk_begin[j] ? 1u : 0u;
     }
     const ChunkInfo c = chunk_info<S>(a, a.stage[stage], chunk, stage);
+    if (c.tau == 0 || c.skip) return;       // uniform over the workgroup: nothing to tune, or no gradient arrived
     float acc0 = 0.f, acc1 = 0.f;
-    if (c.tau >= 1 && !c.skip) {       // uniform over the workgroup
+    {
         const uint32_t oldest = (c.head + c.R - c.tau) % c.R;
         const char *g_ptr = static_cast<const char *>(a.grads) + c.flat_elem0 * S::kStoreBytes;
         const char *v0 = c.arena + (uint64_t)oldest * c.slot_bytes;
@@ -704,13 +770,13 @@ __global__ void __launch_bounds__(kThreads) lambda_state_kernel(const StepArgs a
         char *va_ptr = reinterpret_cast<char *>(a.v_a) + c.flat_elem0 * 4;
         const float alpha = a.alpha, beta = 1.0f - a.alpha;
         for (uint32_t vec = threadIdx.x; vec < c.n_vecs; vec += kThreads) {
-            const Raw rg = ld_off<Raw>(g_ptr, vec * RB), r0 = ld_off<Raw>(v0, vec * RB),
-                      r1 = ld_off<Raw>(v1, vec * RB);
+            const Raw rg = ld_off<S::kNT, Raw>(g_ptr, vec * RB), r0 = ld_off<S::kNT, Raw>(v0, vec * RB),
+                      r1 = ld_off<S::kNT, Raw>(v1, vec * RB);
             v4f vr[S::kF4], va[S::kF4];
 #pragma unroll
             for (int q = 0; q < S::kF4; ++q) {
-                vr[q] = ld_off<v4f>(vr_ptr, vec * FB + 16u * q);
-                va[q] = ld_off<v4f>(va_ptr, vec * FB + 16u * q);
+                vr[q] = ld_off<S::kNT, v4f>(vr_ptr, vec * FB + 16u * q);
+                va[q] = ld_off<S::kNT, v4f>(va_ptr, vec * FB + 16u * q);
             }
             float g[E], w0[E], w1[E];
             S::widen(rg, g);
@@ -727,85 +793,56 @@ __global__ void __launch_bounds__(kThreads) lambda_state_kernel(const StepArgs a
                     r[i] = fmaf(alpha, r[i], beta * gi);
                     s4[i] = fmaf(alpha, s4[i], beta * (gi * gi * (w1[4 * q + i] - w0[4 * q + i])));
                 }
-                st_off(vr_ptr, vec * FB + 16u * q, make_v4f(r[0], r[1], r[2], r[3]));
-                st_off(va_ptr, vec * FB + 16u * q, make_v4f(s4[0], s4[1], s4[2], s4[3]));
+                st_off<S::kNT>(vr_ptr, vec * FB + 16u * q, make_v4f(r[0], r[1], r[2], r[3]));
+                st_off<S::kNT>(va_ptr, vec * FB + 16u * q, make_v4f(s4[0], s4[1], s4[2], s4[3]));
             }
         }
     }
     const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
     const float s0 = wave_sum(acc0), s1 = wave_sum(acc1);
-    if (lane == 0) { red[0][wave] = s0; red[1][wave] = s1; }
+    if (lane == 0) { lds.red[0][wave] = s0; lds.red[1][wave] = s1; }
     __syncthreads();
     if (threadIdx.x < 2) {
         float s = 0.f;
 #pragma unroll
-        for (int w = 0; w < kWaves; ++w) s += red[threadIdx.x][w];
+        for (int w = 0; w < kWaves; ++w) s += lds.red[threadIdx.x][w];
         a.partials[(size_t)threadIdx.x * a.n_chunks + chunk] = s;
     }
 }
 
 #if FERRET_TU_COMMON
-// One workgroup per stage: sums the stage's two series in fp64 in a fixed order and takes the
-// gradient-descent step  lambda <- lambda + 2 eta_lambda ((1-alpha) <v_a, g_0 - v_r> - lambda <v_a, v_a>).
-constexpr int kLambdaThreads = 1024;
-__global__ void __launch_bounds__(kLambdaThreads) lambda_step_kernel(const StepArgs a) {
-    __shared__ double red[2][kLambdaThreads / 64];
+// The two per-stage reductions, each a kernel of its own after the pass that wrote the partials: one workgroup
+// of 1024 lanes per stage (and series).  (Forming the sums inside the step kernel instead, by the last of a
+// stage's workgroups to arrive, was measured on MI355X and is slower: the arrival count needs one device-scope
+// atomic per workgroup, and 42 000 of those on one address take 545 us; spread over 16 counters per stage on
+// separate cache lines they still cost, together with the wait for the partial's store to be acknowledged,
+// 12 us of a 306 us kernel, more than the 7 us that the second launch and its gap cost.)
+__global__ void __launch_bounds__(kSumLanes) lambda_step_kernel(const StepArgs a) {
+    __shared__ double red[kSeries][kSumWaves];
     const uint32_t j = blockIdx.x;
     if (a.stage[j].tau == 0 || ((a.accum || a.masked) && a.mode[j] == 0)) return;     // nothing to tune, or no gradient arrived
     const uint32_t c0 = a.stage[j].chunk_begin;
     const uint32_t c1 = j + 1 < a.n_stages ? a.stage[j + 1].chunk_begin : a.n_chunks;
     // the two series: 0 and 1 when the state pass produced them, 3 and 4 when the fused step did
-    const float *dots = a.partials + (size_t)(a.fused_lambda ? 3u : 0u) * a.n_chunks;
-    double s0 = 0.0, s1 = 0.0;
-    for (uint32_t c = c0 + threadIdx.x; c < c1; c += kLambdaThreads) {
-        s0 += (double)dots[c];
-        s1 += (double)dots[(size_t)a.n_chunks + c];
-    }
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) { s0 += __shfl_xor(s0, off, 64); s1 += __shfl_xor(s1, off, 64); }
-    if ((threadIdx.x & 63u) == 0) { red[0][threadIdx.x >> 6] = s0; red[1][threadIdx.x >> 6] = s1; }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        double dot_a_dr = 0.0, dot_a_a = 0.0;
-        for (int w = 0; w < kLambdaThreads / 64; ++w) { dot_a_dr += red[0][w]; dot_a_a += red[1][w]; }
-        dot_a_dr *= (double)(1.0f - a.alpha);
-        const double lambda = (double)a.lambda_dev[j];
-        a.lambda_dev[j] = (float)(lambda + 2.0 * (double)a.eta_lambda * (dot_a_dr - lambda * dot_a_a));
-    }
+    double total[2];
+    ordered_sums<2, kSumLanes>(a.partials + (size_t)(a.fused_lambda ? 3u : 0u) * a.n_chunks, a.n_chunks, c0, c1, red, total);
+    if (threadIdx.x == 0)
+        a.lambda_dev[j] = lambda_descent_step(a.lambda_dev[j], total[0], total[1], a.alpha, a.eta_lambda);
 }
 
-// Sum the per-chunk partials of each stage in a fixed order, in fp64.  Grid = (stage, series):
-// one workgroup adds up one of the three series of one stage.  Lane t takes chunks t, t+1024, ...
-// (all loads independent), then the 1024 lane sums are combined by a fixed shuffle tree and a
-// fixed order across wavefronts, so the result does not depend on how the step kernel was launched.
-constexpr int kFinalizeThreads = 1024;
-__global__ void __launch_bounds__(kFinalizeThreads) norms_finalize_kernel(const StepArgs a, float *norms_out) {
-    __shared__ double red[kFinalizeThreads / 64];
+// Grid = (stage, series): one workgroup adds up one of the three norm series of one stage.
+__global__ void __launch_bounds__(kSumLanes) norms_finalize_kernel(const StepArgs a) {
+    __shared__ double red[kSeries][kSumWaves];
     const uint32_t j = blockIdx.x, k = blockIdx.y;
     if ((a.accum || a.masked) && a.mode[j] == 0) {       // the stage took no part: no partials were written for it
-        if (threadIdx.x == 0) norms_out[j * 3 + k] = 0.f;
+        if (threadIdx.x == 0) a.norms_out[j * 3 + k] = 0.f;
         return;
     }
     const uint32_t c0 = a.stage[j].chunk_begin;
     const uint32_t c1 = j + 1 < a.n_stages ? a.stage[j + 1].chunk_begin : a.n_chunks;
-    const float *series = a.partials + (size_t)k * a.n_chunks;
-    double s = 0.0;
-    uint32_t c = c0 + threadIdx.x;
-    for (; c + 3 * kFinalizeThreads < c1; c += 4 * kFinalizeThreads) {
-        const float x0 = series[c], x1 = series[c + kFinalizeThreads], x2 = series[c + 2 * kFinalizeThreads],
-                    x3 = series[c + 3 * kFinalizeThreads];
-        s += (double)x0; s += (double)x1; s += (double)x2; s += (double)x3;
-    }
-    for (; c < c1; c += kFinalizeThreads) s += (double)series[c];
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off, 64);
-    if ((threadIdx.x & 63u) == 0) red[threadIdx.x >> 6] = s;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        double total = 0.0;
-        for (int w = 0; w < kFinalizeThreads / 64; ++w) total += red[w];
-        norms_out[j * 3 + k] = (float)total;
-    }
+    double total[1];
+    ordered_sums<1, kSumLanes>(a.partials + (size_t)k * a.n_chunks, a.n_chunks, c0, c1, red, total);
+    if (threadIdx.x == 0) a.norms_out[j * 3 + k] = (float)total[0];
 }
 
 // ---- push: fp32 source -> ring slot (+ master) ----------------------------------------------------
@@ -824,9 +861,10 @@ __global__ void __launch_bounds__(kThreads) push_kernel(const PushArgs a) {
         while (stage + 1 < a.n_stages && chunk >= tab[stage + 1].chunk_begin) ++stage;
         stage = uniform(stage);
         const StageDesc &d = tab[stage];
-        const uint64_t e0 = (uint64_t)(chunk - uniform(d.chunk_begin)) * a.chunk_elems;
+        const uint32_t chunk_elems = uniform(d.chunk_elems);
+        const uint64_t e0 = (uint64_t)(chunk - uniform(d.chunk_begin)) * chunk_elems;
         const uint64_t left = uniform(d.n_elems) - e0;
-        const uint32_t n_here = left < a.chunk_elems ? (uint32_t)left : a.chunk_elems;
+        const uint32_t n_here = left < chunk_elems ? (uint32_t)left : chunk_elems;
         const uint64_t flat0 = uniform(d.flat_off) + e0;
         const uint64_t ring0 = uniform(d.ring_base) + (uint64_t)uniform((uint32_t)d.head) * uniform(d.slot_stride) + e0;
         const float4 *src = reinterpret_cast<const float4 *>(a.src + flat0);
@@ -855,10 +893,10 @@ __global__ void __launch_bounds__(kThreads) copy_kernel(v4u *dst, const v4u *src
     v4u x[kCopyVecsPerLane];
 #pragma unroll
     for (int u = 0; u < kCopyVecsPerLane; ++u)
-        if (base + (size_t)u * kThreads < n_vecs) x[u] = ld(&src[base + (size_t)u * kThreads]);
+        if (base + (size_t)u * kThreads < n_vecs) x[u] = ld<true>(&src[base + (size_t)u * kThreads]);
 #pragma unroll
     for (int u = 0; u < kCopyVecsPerLane; ++u)
-        if (base + (size_t)u * kThreads < n_vecs) st(&dst[base + (size_t)u * kThreads], x[u]);
+        if (base + (size_t)u * kThreads < n_vecs) st<true>(&dst[base + (size_t)u * kThreads], x[u]);
 }
 
 // Plain streaming read with the same shape; the data is summed and compared with a value it never has.
@@ -868,7 +906,7 @@ __global__ void __launch_bounds__(kThreads) read_kernel(const v4u *src, size_t n
 #pragma unroll
     for (int u = 0; u < kCopyVecsPerLane; ++u) {
         x[u] = v4u{0u, 0u, 0u, 0u};
-        if (base + (size_t)u * kThreads < n_vecs) x[u] = ld(&src[base + (size_t)u * kThreads]);
+        if (base + (size_t)u * kThreads < n_vecs) x[u] = ld<true>(&src[base + (size_t)u * kThreads]);
     }
     v4u s = x[0];
 #pragma unroll
@@ -890,11 +928,11 @@ __global__ void __launch_bounds__(kThreads) mix_kernel(char *dst, const char *sr
     for (uint32_t vec = threadIdx.x; vec < here; vec += kThreads) {
         v4f x[NR];
 #pragma unroll
-        for (int i = 0; i < NR; ++i) x[i] = ld_off<v4f>(s0 + (size_t)i * stride, vec * 16u);
+        for (int i = 0; i < NR; ++i) x[i] = ld_off<true, v4f>(s0 + (size_t)i * stride, vec * 16u);
         v4f sum = x[0];
 #pragma unroll
         for (int i = 1; i < NR; ++i) sum += x[i];
-        st_off(d0, vec * 16u, sum);
+        st_off<true>(d0, vec * 16u, sum);
     }
 }
 
@@ -994,24 +1032,22 @@ static uint32_t reserve_lds_for_cap(const ferret_plan &plan, const StepArgs &a, 
     if (cap == 0) {
         // default: cap only steps whose traffic is far beyond the memory-side cache; steps that run out
         // of that cache are latency-bound instead and want every wave they can get
-        // Bytes one lane-vector's worth of a chunk has in flight at once, per element, for each stage; the
-        // cap is taken from the stage at the traffic-weighted median, because workgroups are dispatched in
-        // chunk order and mostly one stage's chunks are resident at a time.
+        // Bytes one chunk of each stage moves; the cap is taken from the stage at the traffic-weighted median,
+        // because workgroups are dispatched in chunk order and mostly one stage's chunks are resident at a time.
         const uint64_t sb = plan.prec == FERRET_F32 ? 4 : 2;
         uint64_t total = 0;
-        uint64_t per_elem[FERRET_MAX_STAGES], traffic[FERRET_MAX_STAGES];
+        uint64_t block[FERRET_MAX_STAGES], traffic[FERRET_MAX_STAGES];
         uint32_t order[FERRET_MAX_STAGES], n = 0;
         for (uint32_t j = 0; j < a.n_stages; ++j) {
             if ((a.accum || a.masked) && a.mode[j] == 0) continue;
             const uint32_t kp = a.stage[j].kp;
             // versions loaded together: all K'+1 on the unrolled paths; on the streamed one a batch counts (measured
             // with its two register sets used in turn: best cap 3-4 for bf16, 2-3 for fp32, which this reproduces)
-            const uint32_t versions = kp <= (uint32_t)kUnrolledItersMid ? kp + 1u : (uint32_t)kStreamBatch;
-            uint64_t per = sb * (versions + 2u) + (plan.prec == FERRET_F32 ? 0u : 8u);
+            uint64_t per = (uint64_t)inflight_bytes_per_elem(plan.prec, (int32_t)kp);
             if (kp == 0 && a.stage[j].tau > 0 && (a.partials || a.penalized)) per += sb;   // V[0] for the gap
             if (a.fused_lambda && a.stage[j].tau > 0) per += sb + 8;   // V[1], v_r, v_a
             if (a.accum) per += 8 - sb;     // running sum read + written; most arrivals write no version (measured: 3 at K' = 3)
-            per_elem[n] = per;
+            block[n] = per * a.stage[j].chunk_elems;
             traffic[n] = a.stage[j].n_elems * (sb * (kp + 3u) + (plan.prec == FERRET_F32 ? 0u : 8u) +
                                                (a.fused_lambda && a.stage[j].tau > 0 ? sb + 16u : 0u));
             total += traffic[n];
@@ -1019,23 +1055,21 @@ static uint32_t reserve_lds_for_cap(const ferret_plan &plan, const StepArgs &a, 
             ++n;
         }
         if (total <= kCapThresholdBytes || n == 0) return 0;
-        for (uint32_t i = 1; i < n; ++i)                      // insertion sort by bytes per element
-            for (uint32_t k = i; k > 0 && per_elem[order[k]] < per_elem[order[k - 1]]; --k) {
+        for (uint32_t i = 1; i < n; ++i)                      // insertion sort by bytes per chunk
+            for (uint32_t k = i; k > 0 && block[order[k]] < block[order[k - 1]]; --k) {
                 const uint32_t t = order[k]; order[k] = order[k - 1]; order[k - 1] = t;
             }
-        uint64_t seen = 0, median_per = per_elem[order[n - 1]];
+        uint64_t seen = 0, block_bytes = block[order[n - 1]];
         for (uint32_t i = 0; i < n; ++i) {
             seen += traffic[order[i]];
-            if (2 * seen >= total) { median_per = per_elem[order[i]]; break; }
+            if (2 * seen >= total) { block_bytes = block[order[i]]; break; }
         }
-        const uint64_t block_bytes = (uint64_t)a.chunk_elems * median_per;
         cap = (int32_t)((kInFlightTargetBytes + block_bytes - 1) / block_bytes);
         if (cap < 2) cap = 2;
         if (cap >= 8) return 0;                               // 8 fit anyway
     }
-    // what step_kernel declares itself: the reduction buffer, and the stage table of the persistent variant
-    const uint32_t used = (persistent ? (uint32_t)sizeof(StageDesc) * FERRET_MAX_STAGES : 0u) +
-                          (uint32_t)(kSeries * kWaves * sizeof(float));
+    // what step_kernel declares itself: the reduction buffers, and the stage table of the persistent variant
+    const uint32_t used = (persistent ? (uint32_t)sizeof(StageDesc) * FERRET_MAX_STAGES : 0u) + (uint32_t)sizeof(StepLds);
     return dyn_lds_for_cap(cap, used);
 }
 
@@ -1126,13 +1160,15 @@ static hipError_t launch_step_typed(const StepArgs &a, int level, bool norms, bo
 // What launch_step has decided; the per-type halves below turn it into the kernel launch.
 struct StepLaunch {
     bool persistent, norms, gout, elide;
+    bool cached;         // ordinary cached accesses instead of non-temporal ones (plain step at the smallest level only)
     int level;
     uint32_t chunks;     // chunks the launch covers (one workgroup each unless persistent)
     uint32_t grid, lds;
 };
 
-template <typename S>
+template <typename S, typename SCached>
 static hipError_t launch_step_for(const StepArgs &a, const StepLaunch &l, hipStream_t st) {
+    if (l.cached) return launch_step_level<SCached, false, 0>(a, l.norms, l.gout, false, l.grid, l.lds, st);
     if (a.fused_lambda && a.accum) return launch_step_accum_fused<S>(a, l.norms, l.gout, l.chunks, l.lds, st);
     if (a.fused_lambda) return launch_step_fused<S>(a, l.level, l.norms, l.gout, l.chunks, l.lds, st);
     if (a.penalized) return launch_step_penalized<S>(a, l.norms, l.gout, l.chunks, l.lds, st);
@@ -1151,28 +1187,29 @@ hipError_t launch_step_bf16(const StepArgs &a, const StepLaunch &l, hipStream_t 
 hipError_t launch_state_f32(const StepArgs &a, uint32_t lds, hipStream_t st);
 hipError_t launch_state_bf16(const StepArgs &a, uint32_t lds, hipStream_t st);
 #if FERRET_TU_F32
-hipError_t launch_step_f32(const StepArgs &a, const StepLaunch &l, hipStream_t st) { return launch_step_for<F32Store>(a, l, st); }
+hipError_t launch_step_f32(const StepArgs &a, const StepLaunch &l, hipStream_t st) { return launch_step_for<F32Store, F32StoreCached>(a, l, st); }
 hipError_t launch_state_f32(const StepArgs &a, uint32_t lds, hipStream_t st) { return launch_state_for<F32Store>(a, lds, st); }
 #endif
 #if FERRET_TU_BF16
-hipError_t launch_step_bf16(const StepArgs &a, const StepLaunch &l, hipStream_t st) { return launch_step_for<Bf16Store>(a, l, st); }
+hipError_t launch_step_bf16(const StepArgs &a, const StepLaunch &l, hipStream_t st) { return launch_step_for<Bf16Store, Bf16StoreCached>(a, l, st); }
 hipError_t launch_state_bf16(const StepArgs &a, uint32_t lds, hipStream_t st) { return launch_state_for<Bf16Store>(a, lds, st); }
 #endif
 
 #if FERRET_TU_COMMON
-int launch_step(const ferret_plan &plan, const StepArgs &a, float *norms_out, void *stream) {
-    if (a.n_chunks == 0) return 0;
+int launch_step(const ferret_plan &plan, const StepArgs &args, void *stream) {
+    if (args.n_chunks == 0) return 0;
     int err = 0;
-    const uint32_t n_launch = a.chunk_end - a.chunk_base;     // 0: no stage takes part, only the norms are cleared
+    const uint32_t n_launch = args.chunk_end - args.chunk_base;     // 0: no stage takes part, only the norms are cleared
     const uint32_t grid = grid_for(plan, n_launch, &err);
     if (err) return err;
     hipStream_t st = static_cast<hipStream_t>(stream);
+    const StepArgs &a = args;
     int streamed = 0;    // kernel level: which K' the launch has to cover
     for (uint32_t j = 0; j < a.n_stages; ++j) {
         const int need = a.stage[j].kp <= kUnrolledItersSmall ? 0 : (a.stage[j].kp <= kUnrolledItersMid ? 1 : 2);
         streamed = need > streamed ? need : streamed;
     }
-    const bool norms = norms_out != nullptr, gout = a.grad_out != nullptr;
+    const bool norms = a.norms_out != nullptr, gout = a.grad_out != nullptr;
     const bool timed = g_prof.on && g_prof.used < (int32_t)g_prof.start.size();
     if (timed) (void)hipEventRecord(g_prof.start[g_prof.used], st);
     StepLaunch l;
@@ -1182,26 +1219,29 @@ int launch_step(const ferret_plan &plan, const StepArgs &a, float *norms_out, vo
     l.gout = gout;
     l.elide = plan.newest_from_master != 0;
     l.level = streamed;
-    l.grid = grid;
+    l.grid = l.persistent ? grid : n_launch;
     l.lds = reserve_lds_for_cap(plan, a, l.persistent);
+    const uint64_t working_set = working_set_bytes(plan.prec, plan.ring_elems, plan.flat_elems);
+    l.cached = !l.persistent && streamed == 0 && !a.accum && !a.penalized && !a.fused_lambda && !a.lambda_dev && !l.elide &&
+               plan.cache_policy != 2 && (plan.cache_policy == 1 || working_set <= kCacheResidentBytes);
     hipError_t e = hipSuccess;
     if (n_launch > 0) e = plan.prec == FERRET_F32 ? launch_step_f32(a, l, st) : launch_step_bf16(a, l, st);
     if (timed) (void)hipEventRecord(g_prof.stop[g_prof.used++], st);
     if (e != hipSuccess) return (int)e;
     if (a.fused_lambda) {       // lambda takes its step for the next call
-        hipLaunchKernelGGL(lambda_step_kernel, dim3(a.n_stages), dim3(kLambdaThreads), 0, st, a);
+        hipLaunchKernelGGL(lambda_step_kernel, dim3(a.n_stages), dim3(kSumLanes), 0, st, a);
         e = hipGetLastError();
         if (e != hipSuccess) return (int)e;
     }
     if (norms) {
-        hipLaunchKernelGGL(norms_finalize_kernel, dim3(a.n_stages, 3), dim3(kFinalizeThreads), 0, st, a, norms_out);
+        hipLaunchKernelGGL(norms_finalize_kernel, dim3(a.n_stages, 3), dim3(kSumLanes), 0, st, a);
         e = hipGetLastError();
     }
     return (int)e;
 }
 
-int launch_lambda_update(const ferret_plan &plan, const StepArgs &a, void *stream) {
-    if (a.n_chunks == 0 || a.chunk_end == a.chunk_base) return 0;
+int launch_lambda_update(const ferret_plan &plan, const StepArgs &args, void *stream) {
+    if (args.n_chunks == 0 || args.chunk_end == args.chunk_base) return 0;
     hipStream_t st = static_cast<hipStream_t>(stream);
     // same kind of resident-workgroup rule as the step (measured optimum for this pass: 2 workgroups per
     // CU at fp32, 352 us against 381 us uncapped at the ViT-B-sized workload); it moves 3 storage elements +
@@ -1209,20 +1249,25 @@ int launch_lambda_update(const ferret_plan &plan, const StepArgs &a, void *strea
     uint32_t lds = 0;
     {
         const uint64_t per = (plan.prec == FERRET_F32 ? 4u : 2u) * 3u + 16u;
-        uint64_t bytes = 0;
-        for (uint32_t j = 0; j < a.n_stages; ++j)
-            if (a.stage[j].tau >= 1 && !((a.accum || a.masked) && a.mode[j] == 0)) bytes += a.stage[j].n_elems * per;
+        uint64_t bytes = 0, elems = 0, weighted = 0;
+        for (uint32_t j = 0; j < args.n_stages; ++j)
+            if (args.stage[j].tau >= 1 && !((args.accum || args.masked) && args.mode[j] == 0)) {
+                bytes += args.stage[j].n_elems * per;
+                elems += args.stage[j].n_elems;
+                weighted += args.stage[j].n_elems * args.stage[j].chunk_elems;
+            }
+        const uint64_t chunk_elems = elems ? weighted / elems : 1;     // size-weighted mean over the stages that take part
         const int32_t env = plan.resident_cap;
         int32_t cap = env != 0 ? env : (bytes > kCapThresholdBytes
-                                            ? (int32_t)((kStateTargetBytes + a.chunk_elems * per - 1) / (a.chunk_elems * per)) : -1);
+                                            ? (int32_t)((kStateTargetBytes + chunk_elems * per - 1) / (chunk_elems * per)) : -1);
         if (cap > 0 && cap < 8) {
             if (cap < 2) cap = 2;
-            lds = dyn_lds_for_cap(cap, (uint32_t)(2 * kWaves * sizeof(float)));   // the kernel's own red[2][kWaves]
+            lds = dyn_lds_for_cap(cap, (uint32_t)sizeof(StepLds));
         }
     }
-    hipError_t e = plan.prec == FERRET_F32 ? launch_state_f32(a, lds, st) : launch_state_bf16(a, lds, st);
+    hipError_t e = plan.prec == FERRET_F32 ? launch_state_f32(args, lds, st) : launch_state_bf16(args, lds, st);
     if (e != hipSuccess) return (int)e;
-    hipLaunchKernelGGL(lambda_step_kernel, dim3(a.n_stages), dim3(kLambdaThreads), 0, st, a);
+    hipLaunchKernelGGL(lambda_step_kernel, dim3(args.n_stages), dim3(kSumLanes), 0, st, args);
     return (int)hipGetLastError();
 }
 

@@ -185,49 +185,54 @@ def custom_workload(name, tensor_numels_per_stage, staleness, ring_depth, n_iter
 # ----------------------------------------------------------------------------------------
 # random draws
 # ----------------------------------------------------------------------------------------
-def _gen(seed: int, stage: int, stream: int) -> torch.Generator:
-    g = torch.Generator(device="cpu")
+def _gen(seed: int, stage: int, stream: int, device="cpu") -> torch.Generator:
+    g = torch.Generator(device=device)
     g.manual_seed((seed * 4099 + stage) * 1_000_003 + stream)
     return g
 
 
 def _normal(n: int, std: float, gen: torch.Generator) -> torch.Tensor:
-    x = torch.empty(n, dtype=torch.float32)
+    x = torch.empty(n, dtype=torch.float32, device=gen.device)
     x.normal_(0.0, std, generator=gen)
     return x
 
 
-def draw_grads(w: Workload, j: int, n: int, amplified: bool = False, step: int = 0) -> torch.Tensor:
+def draw_grads(w: Workload, j: int, n: int, amplified: bool = False, step: int = 0, device="cpu") -> torch.Tensor:
     """Gradient of stage j for optimisation step `step` (fp32 values; caller rounds)."""
     std = 1.0 if amplified else w.grad_std
-    g = _normal(n, std, _gen(w.seed, j, 1 + 1000 * step))
+    g = _normal(n, std, _gen(w.seed, j, 1 + 1000 * step, device))
     if w.heavy_tail is not None:
         p, scale = w.heavy_tail
-        mask = torch.empty(n, dtype=torch.float32).uniform_(0, 1, generator=_gen(w.seed, j, 99 + 1000 * step)) < p
+        u = torch.empty(n, dtype=torch.float32, device=g.device)
+        mask = u.uniform_(0, 1, generator=_gen(w.seed, j, 99 + 1000 * step, device)) < p
         g[mask] *= scale
     return g
 
 
 def generate_stage(w: Workload, j: int, amplified: bool = False,
-                   n_versions: Optional[int] = None) -> StageData:
-    """Versions (oldest first), gradient and master of stage j, as flat logical arrays."""
+                   n_versions: Optional[int] = None, device="cpu") -> StageData:
+    """Versions (oldest first), gradient and master of stage j, as flat logical arrays.
+
+    device="cpu" (default) draws with torch's CPU generators: bit-reproducible everywhere, what every parity
+    test uses.  Another device draws the same recipe with that device's generator (same seeds, different
+    streams): for timing runs of the largest workload, where only the distributions matter."""
     n = w.stage_numel()[j]
     R = w.ring_depth if n_versions is None else n_versions
     drift_std = 0.05 if amplified else w.drift_std
     bf16 = w.precision == "bf16"
 
-    W = _normal(n, w.weight_std, _gen(w.seed, j, 0))
+    W = _normal(n, w.weight_std, _gen(w.seed, j, 0, device))
     master = W.clone() if bf16 else None
     newest = W.to(torch.bfloat16) if bf16 else W
     versions = [newest]
     for k in range(R - 2, -1, -1):           # version step k: between versions k and k+1
-        d = _normal(n, drift_std, _gen(w.seed, j, 2 + k))
+        d = _normal(n, drift_std, _gen(w.seed, j, 2 + k, device))
         if bf16:
             older = (versions[0].to(torch.float32) - d).to(torch.bfloat16)
         else:
             older = versions[0] - d
         versions.insert(0, older)
-    g = draw_grads(w, j, n, amplified)
+    g = draw_grads(w, j, n, amplified, device=device)
     if bf16:
         g = g.to(torch.bfloat16)
     return StageData(versions, g, master)

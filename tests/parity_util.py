@@ -8,10 +8,16 @@ Tolerances (written here once, used by every parity test):
       that cancel to (almost) zero, where a relative bound has no meaning.
   bf16 outputs (new version):                bit-exact round-to-nearest-even of the device's own
       fp32 master, and at most 1 bf16 ulp from the oracle's value: both sides round their fp32
-      master, so they differ only when the two masters straddle a rounding boundary.  For an
-      element whose update cancels to (almost) zero the masters themselves differ by up to the
-      fp32 bound's absolute part, 1e-5 * rms(master), which at that magnitude is many bf16
-      steps; the bound is therefore  |gpu - ref| <= ulp_bf16(ref) + 1e-5 * rms(ref master).
+      master, so they differ only when the two masters straddle a rounding boundary.  The two
+      masters themselves differ by the fp32 arithmetic of the update, bounded per element by
+          d = 8 * 2^-24 * (|m'| + |eta| * (K'+1) * |step|)         (master_slack below)
+      (oracle: fp64 rounded once, 2^-25 |m'|; device: one fused multiply-add m - eta*step, 2^-24 |m'|,
+      on a step that went through K' iterations of three to four fp32 roundings each, i.e. at most
+      about 4 (K'+1) 2^-24 |step|; the factor 8 leaves a margin of two).  An element whose update
+      cancels to almost zero can sit many bf16 steps of its own tiny magnitude away and still be
+      within d, so the bound is  |gpu - ref| <= ulp_bf16(ref) + d;  the device master is held to
+      |gpu - ref| <= d as well.  Every check reports how many elements differ at all and how many
+      needed d (were further than one bf16 ulp from the oracle).
   norms:                                     relative 1e-5 against the oracle's fp64 sums
 """
 from __future__ import annotations
@@ -58,8 +64,35 @@ def bf16_bits_to_f64(bits):
     return (np.asarray(bits, dtype=np.uint16).astype(np.uint32) << 16).view(np.float32).astype(np.float64)
 
 
+EPS32 = 2.0 ** -24
+BF16_REPORT = []        # (what, elements, differing bit patterns, elements beyond one bf16 ulp): filled by every check
+
+
+def master_slack(ref_master, lr, step_mag, kp, extra=0.0):
+    """Per-element bound on |device fp32 master - oracle fp32 master| from the arithmetic of the update
+    (module docstring).  step_mag: magnitude of what eta multiplies (the compensated gradient, or the scaled
+    running sum); kp: iterations it went through; extra: further per-element terms a caller can justify."""
+    m = np.abs(np.asarray(ref_master, dtype=np.float64))
+    m = np.where(np.isfinite(m), m, 0.0)
+    g = np.abs(np.asarray(step_mag, dtype=np.float64))
+    g = np.where(np.isfinite(g), g, 0.0)
+    return 8.0 * EPS32 * (m + abs(float(lr)) * (kp + 1) * g) + extra
+
+
+def assert_master_within_slack(got_master, ref_master, slack, what):
+    got = np.asarray(got_master, dtype=np.float64)
+    ref = np.asarray(ref_master, dtype=np.float64)
+    finite = np.isfinite(ref) & np.isfinite(got)
+    err = np.abs(got - ref)[finite]
+    lim = np.broadcast_to(slack, ref.shape)[finite]
+    bad = err > lim
+    assert not bad.any(), (f"{what}: {int(bad.sum())} of {err.size} master elements beyond the derived fp32 bound; worst "
+                           f"error {err[np.argmax(err - lim)]:.3g} against {lim[np.argmax(err - lim)]:.3g}")
+
+
 def assert_bf16_within_one_ulp(got_bits, ref_bits, what, abs_slack=0.0):
-    """|gpu - ref| <= one bf16 step at ref's magnitude + abs_slack (see the module docstring)."""
+    """|gpu - ref| <= one bf16 step at ref's magnitude + abs_slack (scalar or per element; see the module
+    docstring).  Records and returns how many elements needed the slack."""
     got_bits = np.asarray(got_bits, dtype=np.uint16)
     ref_bits = np.asarray(ref_bits, dtype=np.uint16)
     def isnan(b):
@@ -76,10 +109,17 @@ def assert_bf16_within_one_ulp(got_bits, ref_bits, what, abs_slack=0.0):
     expo = np.floor(np.log2(np.maximum(np.abs(ref), 2.0 ** -126)))
     ulp = 2.0 ** (expo - 7)
     err = np.abs(got - ref)
-    bad = err > ulp + abs_slack
-    assert not bad.any(), (f"{what}: {int(bad.sum())} of {err.size} elements beyond 1 bf16 ulp "
-                           f"(+{abs_slack:.3g}); worst got {got[np.argmax(err - ulp)]!r} ref {ref[np.argmax(err - ulp)]!r}")
-    return float((got_bits != ref_bits).mean()) if got_bits.size else 0.0
+    slack = np.broadcast_to(np.asarray(abs_slack, dtype=np.float64), got_bits.shape)[ok][~inf]
+    bad = err > ulp + slack
+    assert not bad.any(), (f"{what}: {int(bad.sum())} of {err.size} elements beyond 1 bf16 ulp + the derived slack; "
+                           f"worst got {got[np.argmax(err - ulp - slack)]!r} ref {ref[np.argmax(err - ulp - slack)]!r} "
+                           f"slack {slack[np.argmax(err - ulp - slack)]:.3g}")
+    n_diff, n_beyond = int((got_bits != ref_bits).sum()), int((err > ulp).sum())
+    BF16_REPORT.append((what, int(got_bits.size), n_diff, n_beyond))
+    if got_bits.size >= 1_000_000 or n_beyond:
+        print(f"  [bf16] {what}: {got_bits.size} elements, {n_diff} differ from the oracle, {n_beyond} by more than 1 bf16 ulp "
+              f"(within the derived slack)", flush=True)
+    return float(n_diff / got_bits.size) if got_bits.size else 0.0
 
 
 def assert_bf16_is_rounded_master(got_bits, got_master, what):
@@ -157,10 +197,11 @@ def check_step_against_oracle(w, plan, st, host, K=None, lam=None, lr=None, n_th
             got_new = bits_of(st.get_version(j, slot))
             got_m = st.get_flat(st.master, j).numpy()
             stats[f"m{j}"] = assert_close_f32(got_m, ref["master"], tag + " master")
-            m64 = ref["master"].astype(np.float64)
-            rms = float(np.sqrt(np.mean(m64[np.isfinite(m64)] ** 2))) if np.isfinite(m64).any() else 0.0
+            slack = master_slack(ref["master"], w.lr if lr is None else lr, np.maximum(np.abs(ref["g"]), np.abs(host[j].grads.float().numpy())),
+                                 plan.stage_effective_iters(j))
+            assert_master_within_slack(got_m, ref["master"], slack, tag + " master")
             stats[f"w{j}"] = assert_bf16_within_one_ulp(got_new, ref["new"], tag + " new version (bf16)",
-                                                        abs_slack=RTOL * rms)
+                                                        abs_slack=slack)
             assert_bf16_is_rounded_master(got_new, got_m, tag + " new version vs own master")
         np.testing.assert_allclose(norms[j], ref["norms"], rtol=RTOL, atol=1e-30, err_msg=tag + " norms")
         if w.numel > 50_000_000:

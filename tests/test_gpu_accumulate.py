@@ -71,15 +71,16 @@ def test_accumulation_groups_with_varying_staleness(precision):
                                      np.float32(1.0 / 3.0), mode[j] == 2, acc_host[j], bf16=bf16)
             PU.assert_close_f32(st.get_flat(st.grad_out, j).numpy(), ref["g"], tag + " g")
             PU.assert_close_f32(got_acc, ref["accum"], tag + " accum")
-            acc_host[j] = got_acc.copy()
+            acc_before, acc_host[j] = acc_host[j], got_acc.copy()
             if mode[j] == 2:
                 got_new = st.get_version(j, write_slots[j])
                 if bf16:
                     got_m = st.get_flat(st.master, j).numpy()
                     PU.assert_close_f32(got_m, ref["master"], tag + " master")
-                    rms = float(np.sqrt(np.mean(ref["master"].astype(np.float64) ** 2)))
-                    PU.assert_bf16_within_one_ulp(PU.bits_of(got_new), ref["new"], tag + " version",
-                                                  abs_slack=PU.RTOL * rms)
+                    # eta multiplies scale * (running sum + this compensated gradient), scale <= 1
+                    slack = PU.master_slack(ref["master"], w.lr, np.abs(acc_before) + np.abs(ref["g"]), tau + 2)
+                    PU.assert_master_within_slack(got_m, ref["master"], slack, tag + " master")
+                    PU.assert_bf16_within_one_ulp(PU.bits_of(got_new), ref["new"], tag + " version", abs_slack=slack)
                     PU.assert_bf16_is_rounded_master(PU.bits_of(got_new), got_m, tag)
                     master[j] = got_m.copy()
                 else:
@@ -179,15 +180,19 @@ def test_accumulation_with_self_tuned_lambda(precision, fused):
             PU.assert_close_f32(st.get_flat(st.grad_out, j).numpy(), ref["g"], tag + " g")
             got_acc = st.get_flat(accum, j).numpy()
             PU.assert_close_f32(got_acc, ref["accum"], tag + " accum")
+            acc_before = acc_host[j]
             acc_host[j], state[j], lams[j] = got_acc.copy(), (got_r.copy(), got_a.copy()), lam_gpu[j]
             if mode[j] == 2:
                 got_new = st.get_version(j, write_slots[j])
                 if bf16:
                     got_m = st.get_flat(st.master, j).numpy()
                     PU.assert_close_f32(got_m, ref["master"], tag + " master")
-                    rms = float(np.sqrt(np.mean(ref["master"].astype(np.float64) ** 2)))
-                    PU.assert_bf16_within_one_ulp(PU.bits_of(got_new), ref["new"], tag + " version",
-                                                  abs_slack=PU.RTOL * rms)
+                    # eta multiplies scale * (running sum + this compensated gradient), scale <= 1
+                    # lambda_j itself is only held to 1e-5 relative, and the correction g_K' - g_0 scales with it
+                    slack = PU.master_slack(ref["master"], w.lr, np.abs(acc_before) + np.abs(ref["g"]), tau + 2,
+                                            extra=abs(w.lr) * 2e-5 * np.abs(ref["g"].astype(np.float64) - host[j].grads.float().numpy()))
+                    PU.assert_master_within_slack(got_m, ref["master"], slack, tag + " master")
+                    PU.assert_bf16_within_one_ulp(PU.bits_of(got_new), ref["new"], tag + " version", abs_slack=slack)
                     master[j] = got_m.copy()
                 else:
                     PU.assert_close_f32(got_new.numpy(), ref["new"], tag + " version")
@@ -263,15 +268,17 @@ def test_random_accumulation_schedules(seed):
                                          np.float32(scale), mode[j] == 2, acc_host[j], bf16=bf16)
             PU.assert_close_f32(st.get_flat(st.grad_out, j).numpy(), ref["g"], tag + " g")
             PU.assert_close_f32(got_acc, ref["accum"], tag + " accum")
-            acc_host[j] = got_acc.copy()
+            acc_before, acc_host[j] = acc_host[j], got_acc.copy()
             if mode[j] == 2:
                 got_new = st.get_version(j, write_slots[j])
                 if bf16:
                     got_m = st.get_flat(st.master, j).numpy()
                     PU.assert_close_f32(got_m, ref["master"], tag + " master")
-                    rms = float(np.sqrt(np.mean(ref["master"].astype(np.float64) ** 2)))
-                    PU.assert_bf16_within_one_ulp(PU.bits_of(got_new), ref["new"], tag + " version",
-                                                  abs_slack=PU.RTOL * rms)
+                    # eta multiplies scale * (running sum + this compensated gradient), scale <= 1
+                    slack = PU.master_slack(ref["master"], w.lr, np.abs(acc_before) + np.abs(ref["g"]), O.effective_iters(K, tau) + 2,
+                                            extra=abs(w.lr) * 2e-5 * np.abs(ref["g"].astype(np.float64) - host[j].grads.float().numpy()) if adaptive else 0.0)
+                    PU.assert_master_within_slack(got_m, ref["master"], slack, tag + " master")
+                    PU.assert_bf16_within_one_ulp(PU.bits_of(got_new), ref["new"], tag + " version", abs_slack=slack)
                     master[j] = got_m.copy()
                 else:
                     PU.assert_close_f32(got_new.numpy(), ref["new"], tag + " version")

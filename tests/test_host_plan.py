@@ -87,7 +87,39 @@ def test_bf16_plan_sizes(lib):
     assert plan.precision == B.FERRET_BF16_MASTER_F32
     assert plan.ring_bytes == plan.ring_elems * 2 and plan.grad_bytes == plan.flat_elems * 2
     assert plan.master_bytes == plan.flat_elems * 4
-    assert plan.chunk_elems == 2048
+    assert [plan.stage_chunk_elems(j) for j in range(2)] == [2048, 2048] and plan.chunk_elems == 2048     # a small plan
+    # with a byte target: K' = 1 has 2*(2+2)+8 = 16 bytes per element in flight, K' = 0 has 6+8 = 14
+    sized, _ = _plan([[100], [200]], [1, 0], R=2, prec=B.FERRET_BF16_MASTER_F32, tuning=dict(chunk_bytes=48 * 1024))
+    assert [sized.stage_chunk_elems(j) for j in range(2)] == [3072, 3072] and sized.chunk_elems == 3072
+
+
+def test_default_chunks_move_equal_bytes_per_workgroup(lib):
+    """For plans that stream, each stage's chunk is the multiple of 1024 elements nearest to 48 KiB / (bytes per
+    element in flight), so a workgroup moves about the same bytes whatever its stage's K' (hand-computed for the
+    ViT-B-sized workload and for Alg. 1's literal iteration count); plans that fit the memory-side cache keep 2048."""
+    for idx in (1, 2, 3):
+        small = B.plan_for_workload(W.make_workload(idx))
+        assert {small.stage_chunk_elems(j) for j in range(small.n_stages)} == {2048}
+    w = W.make_workload(4)
+    plan = B.plan_for_workload(w)                     # K' = 3,3,3,3,3,2,1,0: 24,24,24,24,24,20,16,12 bytes per element
+    assert [plan.stage_chunk_elems(j) for j in range(8)] == [2048] * 6 + [3072, 4096]
+    assert [plan.stage_n_chunks(j) for j in range(8)] == [-(-plan.stage_numel(j) // plan.stage_chunk_elems(j)) for j in range(8)]
+    assert plan.n_chunks == sum(plan.stage_n_chunks(j) for j in range(8))
+    assert plan.workspace_bytes >= plan.n_chunks * 20
+    full = B.plan_for_workload(w, n_iters=B.FERRET_ITERS_FULL)    # K' = 7..0: 40,36,32,28,24,20,16,12
+    assert [full.stage_chunk_elems(j) for j in range(8)] == [1024, 1024, 2048, 2048, 2048, 2048, 3072, 4096]
+    none = B.plan_for_workload(w, n_iters=0)          # no iterations: V[0] is still read for the weight gap (16 bytes)
+    assert [none.stage_chunk_elems(j) for j in range(8)] == [3072] * 7 + [4096]
+    deep = B.plan_for_workload(W.make_workload(5), n_iters=B.FERRET_ITERS_FULL)
+    # bf16, K' = 15..0: beyond K' = 8 the kernel streams 8 versions at a time: 2*(8+2)+8 = 28 bytes in flight
+    assert [deep.stage_chunk_elems(j) for j in range(7)] == [2048] * 7
+    assert [deep.stage_chunk_elems(j) for j in (12, 13, 14, 15)] == [2048, 3072, 3072, 3072]   # 20, 18, 16, 14 bytes
+    # an explicit size applies to every stage; a byte target scales all of them
+    fixed = B.plan_for_workload(w, chunk_elems=2048)
+    assert [fixed.stage_chunk_elems(j) for j in range(8)] == [2048] * 8 and fixed.n_chunks == 42272
+    big = B.plan_for_workload(w, tuning=dict(chunk_bytes=96 * 1024))
+    assert [big.stage_chunk_elems(j) for j in range(8)] == [4096] * 5 + [5120, 6144, 8192]
+    assert plan.stage_chunk_elems(8) == -1 and plan.stage_n_chunks(-1) == -1
 
 
 def test_minimal_ring_depth_is_paper_count(lib):
@@ -226,6 +258,27 @@ def test_step_and_push_argument_errors(lib):
     assert "master" in B.last_error()
     assert lib.ferret_copy_bytes(16, 16, 8, None) == B.FERRET_EINVAL
     assert lib.ferret_copy_bytes(16, 16, 0, None) == B.FERRET_OK
+
+
+def test_tuning_validation(lib):
+    def bad(**tuning):
+        with pytest.raises(B.FerretError) as e:
+            _plan([[4096]], [1], R=2, prec=tuning.pop("prec", B.FERRET_F32), chunk=tuning.pop("chunk", 0), tuning=tuning)
+        assert e.value.status == B.FERRET_EINVAL
+        return e.value.message
+    assert "resident_cap" in bad(resident_cap=1)              # one workgroup cannot hold more than 64 of 160 KiB
+    assert "resident_cap" in bad(resident_cap=33)
+    assert "cache_policy" in bad(cache_policy=3)
+    assert "chunk_bytes" in bad(chunk_bytes=-1)
+    assert "not both" in bad(chunk_bytes=4096, chunk=1024)
+    assert "persistent" in bad(newest_from_master=1, blocks_per_cu=2, prec=B.FERRET_BF16_MASTER_F32)
+    assert "reserved" in bad(reserved=1)
+    with pytest.raises(ValueError):
+        _plan([[4096]], [1], R=2, tuning=dict(no_such_field=1))
+    for ok in (dict(resident_cap=2), dict(resident_cap=-1), dict(cache_policy=1), dict(cache_policy=2),
+               dict(chunk_bytes=1), dict(chunk_bytes=1 << 30)):
+        plan, _ = _plan([[4096]], [1], R=2, tuning=ok)
+        assert plan.n_chunks >= 1 and plan.stage_chunk_elems(0) % 1024 == 0
 
 
 def test_noalloc_step_rejects_plans_beyond_its_scratch(lib):

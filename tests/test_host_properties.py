@@ -53,7 +53,11 @@ def test_layout_and_state_invariants(sizes, data):
         assert regions[-1][1] <= total and all(a[1] <= b[0] for a, b in zip(regions, regions[1:]))
     assert all(lo % 4 == 0 for lo, _ in flat + ring)                   # 16-byte aligned starts
     assert plan.ring_bytes == plan.ring_elems * elt
-    assert plan.n_chunks == sum(-(-plan.stage_numel(j) // plan.chunk_elems) for j in range(P))
+    assert plan.n_chunks == sum(-(-plan.stage_numel(j) // plan.stage_chunk_elems(j)) for j in range(P))
+    assert all(plan.stage_chunk_elems(j) % 1024 == 0 and plan.stage_chunk_elems(j) >= 1024 for j in range(P))
+    assert plan.chunk_elems == max(plan.stage_chunk_elems(j) for j in range(P))
+    if chunk:
+        assert all(plan.stage_chunk_elems(j) == chunk for j in range(P))
     # ring arithmetic for an arbitrary valid state
     heads = [data.draw(st.integers(0, plan.stage_ring_depth(j) - 1)) for j in range(P)]
     valid = [data.draw(st.integers(1, plan.stage_ring_depth(j))) for j in range(P)]
