@@ -392,12 +392,13 @@ ferret_status ferret_stream_mix(void *dst, const void *src, size_t src_stride_by
 /* ---- measurement ------------------------------------------------------------------------------ */
 /* Per-launch timing of the fused step kernel with HIP events recorded on the step's own stream,
  * immediately before and after that kernel (the norms' finalize kernel is outside the pair).
- * begin: create `capacity` event pairs; from then on every ferret_compensate_step of this process
- *        records one pair until the capacity is used up.
+ * begin: create `capacity` event pairs; from then on every step launched by the CALLING THREAD records one
+ *        pair until the capacity is used up (steps other threads launch meanwhile are not recorded).
+ *        FERRET_ESTATE if a session is already open (one per process at a time).
  * end:   wait for the last recorded pair, write the durations in milliseconds (launch order) to the
  *        host array ms_out[0 .. min(cap, recorded)), store the number recorded in *n_out, destroy the
- *        events.  FERRET_ESTATE if begin was not called.
- * Process-wide, not thread-safe; meant for benchmarks. */
+ *        events.  FERRET_ESTATE if begin was not called, or was called by another thread.
+ * Safe to call from several threads (a mutex guards the session); meant for benchmarks. */
 ferret_status ferret_profile_begin(int32_t capacity);
 ferret_status ferret_profile_end(float *ms_out, int32_t cap, int32_t *n_out);
 

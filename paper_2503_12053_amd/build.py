@@ -1,6 +1,7 @@
 """Build libferret.so (host planner + HIP kernels) for gfx950 with hipcc, in-tree.
 
     python -m paper_2503_12053_amd.build [--force]
+    python -m paper_2503_12053_amd.build --sanitize [dir]     host code under ASan/UBSan and TSan (no GPU needed)
 
 The library lands next to this file so that it travels with the source tree; nothing is
 installed.  hipcc cross-compiles: no GPU is needed to build.
@@ -73,6 +74,29 @@ def compile_jobs(objdir: str) -> list:
     return jobs
 
 
+SANITIZERS = {"address": ["-fsanitize=address,undefined", "-fno-sanitize-recover=all"],
+              "thread": ["-fsanitize=thread"]}
+
+
+def build_sanitized(kind: str, out: str, verbose: bool = False) -> str:
+    """Host-only executable for sanitizer runs (no GPU, no hipcc): the library's host sources, the stand-in launchers
+    and the driver under tests/sanitize/, compiled with the host C++ compiler and -fsanitize=address,undefined
+    (kind "address") or -fsanitize=thread (kind "thread").  Run it as `<out> all` or `<out> planner`; it exits
+    non-zero when one of its checks or the sanitizer fails."""
+    cxx = shutil.which("g++") or shutil.which("c++")
+    if cxx is None:
+        raise RuntimeError("no host C++ compiler found")
+    san = os.path.join(ROOT, "tests", "sanitize")
+    cmd = [cxx, "-std=c++17", "-O1", "-g", "-fno-omit-frame-pointer", *SANITIZERS[kind], "-Wall", "-Wno-unused-parameter",
+           "-I", os.path.join(ROOT, "include"), "-I", CSRC,
+           *[s for s in SOURCES if not s.endswith(".hip")],
+           os.path.join(san, "stub_launchers.cpp"), os.path.join(san, "host_driver.cpp"), "-pthread", "-o", out]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    return out
+
+
 def up_to_date() -> bool:
     if not os.path.exists(LIB):
         return False
@@ -101,5 +125,13 @@ def build(force: bool = False, verbose: bool = True) -> str:
 
 
 if __name__ == "__main__":
+    if "--sanitize" in sys.argv:           # python -m paper_2503_12053_amd.build --sanitize [dir]: build and run both
+        outdir = sys.argv[sys.argv.index("--sanitize") + 1] if len(sys.argv) > sys.argv.index("--sanitize") + 1 \
+            else tempfile.mkdtemp(prefix="ferret_sanitize_")
+        for kind, what in (("address", "all"), ("thread", "planner")):
+            exe = build_sanitized(kind, os.path.join(outdir, f"host_driver_{kind}"), verbose=True)
+            subprocess.run([exe, what], check=True)
+        print("sanitizer runs clean")
+        sys.exit(0)
     build(force="--force" in sys.argv)
     print(LIB)

@@ -417,7 +417,7 @@ ferret_status ferret_push_version(ferret_plan *plan, void *ring, float *master, 
 // takes_part: null = every stage, else per stage non-zero = the stage is read and written by this call
 static ferret_status check_step_args(const char *who, const ferret_plan *plan, void *ring, const void *grads,
                                      float *master, float *norms_out, void *grad_out, void *workspace,
-                                     const int32_t *takes_part) {
+                                     const int32_t *takes_part = nullptr) {
     if (!plan || !ring || !grads) { set_error("%s: null plan, ring or grads", who); return FERRET_EINVAL; }
     const bool mixed = plan->prec == FERRET_BF16_MASTER_F32;
     if (mixed && !master) { set_error("%s: bf16 plan needs the fp32 master", who); return FERRET_EINVAL; }
@@ -434,10 +434,7 @@ static ferret_status check_step_args(const char *who, const ferret_plan *plan, v
         }
     return FERRET_OK;
 }
-static ferret_status check_step_args(const char *who, const ferret_plan *plan, void *ring, const void *grads,
-                                     float *master, float *norms_out, void *grad_out, void *workspace) {
-    return check_step_args(who, plan, ring, grads, master, norms_out, grad_out, workspace, nullptr);
-}
+
 
 // The step's scratch: five per-chunk series.
 static void use_workspace(StepArgs &a, void *workspace) { a.partials = static_cast<float *>(workspace); }
@@ -763,6 +760,7 @@ ferret_status ferret_profile_begin(int32_t capacity) {
 ferret_status ferret_profile_end(float *ms_out, int32_t cap, int32_t *n_out) {
     if (!n_out || cap < 0 || (cap > 0 && !ms_out)) { set_error("profile_end: bad arguments"); return FERRET_EINVAL; }
     int err = profile_end(ms_out, cap, n_out);
+    if (err == -2) { set_error("profile_end: the session belongs to the thread that called profile_begin"); return FERRET_ESTATE; }
     if (err < 0) { set_error("profile_end: profile_begin was not called"); return FERRET_ESTATE; }
     if (err) { set_error("profile_end: %s", device_error_string(err)); return FERRET_EDEVICE; }
     return FERRET_OK;

@@ -28,6 +28,7 @@
 #include <hip/hip_runtime.h>
 
 #include <mutex>
+#include <thread>
 #include <vector>
 
 #include "ferret_internal.h"
@@ -743,7 +744,7 @@ __global__ void __launch_bounds__(kThreads) step_kernel(const StepArgs a) {
 // forms the chunk's share of <v_a, g_0 - v_r> and <v_a, v_a> on the OLD averages and writes the new
 // ones, v_r <- alpha v_r + (1-alpha) g_0 and v_a <- alpha v_a + (1-alpha) g_0 g_0 (V[1]-V[0]).
 // Reads g_0, V[0], V[1] (storage type) and v_r, v_a (fp32) once each: 28 bytes per fp32 parameter.
-// lambda_step_kernel sums the stage's two series afterwards and takes the lambda step.
+// stage_sums_kernel sums the stage's two series afterwards and takes the lambda step.
 template <typename S>
 __global__ void __launch_bounds__(kThreads) lambda_state_kernel(const StepArgs a) {
     using Raw = typename S::Raw;
@@ -811,38 +812,38 @@ __global__ void __launch_bounds__(kThreads) lambda_state_kernel(const StepArgs a
 }
 
 #if FERRET_TU_COMMON
-// The two per-stage reductions, each a kernel of its own after the pass that wrote the partials: one workgroup
-// of 1024 lanes per stage (and series).  (Forming the sums inside the step kernel instead, by the last of a
+// The per-stage reductions, one small kernel after the pass that wrote the partials: one workgroup of 1024 lanes
+// per stage and job.  (Forming the sums inside the step kernel instead, by the last of a
 // stage's workgroups to arrive, was measured on MI355X and is slower: the arrival count needs one device-scope
 // atomic per workgroup, and 42 000 of those on one address take 545 us; spread over 16 counters per stage on
 // separate cache lines they still cost, together with the wait for the partial's store to be acknowledged,
 // 12 us of a 306 us kernel, more than the 7 us that the second launch and its gap cost.)
-__global__ void __launch_bounds__(kSumLanes) lambda_step_kernel(const StepArgs a) {
+// Grid = (stage, job), job = first_job + blockIdx.y: jobs 0..2 add up one of the three norm series of the stage, job 3
+// sums the stage's two lambda series and takes the lambda step.  A launch covers the jobs that are wanted: norms
+// only (0..2), norms and lambda step after a one-pass adaptive step (0..3), or the lambda step alone (3).
+constexpr uint32_t kJobLambda = 3;
+__global__ void __launch_bounds__(kSumLanes) stage_sums_kernel(const StepArgs a, uint32_t first_job) {
     __shared__ double red[kSeries][kSumWaves];
-    const uint32_t j = blockIdx.x;
-    if (a.stage[j].tau == 0 || ((a.accum || a.masked) && a.mode[j] == 0)) return;     // nothing to tune, or no gradient arrived
+    const uint32_t j = blockIdx.x, job = first_job + blockIdx.y;
+    const bool absent = (a.accum || a.masked) && a.mode[j] == 0;     // the stage took no part: nothing was written for it
     const uint32_t c0 = a.stage[j].chunk_begin;
     const uint32_t c1 = j + 1 < a.n_stages ? a.stage[j + 1].chunk_begin : a.n_chunks;
-    // the two series: 0 and 1 when the state pass produced them, 3 and 4 when the fused step did
-    double total[2];
-    ordered_sums<2, kSumLanes>(a.partials + (size_t)(a.fused_lambda ? 3u : 0u) * a.n_chunks, a.n_chunks, c0, c1, red, total);
-    if (threadIdx.x == 0)
-        a.lambda_dev[j] = lambda_descent_step(a.lambda_dev[j], total[0], total[1], a.alpha, a.eta_lambda);
-}
-
-// Grid = (stage, series): one workgroup adds up one of the three norm series of one stage.
-__global__ void __launch_bounds__(kSumLanes) norms_finalize_kernel(const StepArgs a) {
-    __shared__ double red[kSeries][kSumWaves];
-    const uint32_t j = blockIdx.x, k = blockIdx.y;
-    if ((a.accum || a.masked) && a.mode[j] == 0) {       // the stage took no part: no partials were written for it
-        if (threadIdx.x == 0) a.norms_out[j * 3 + k] = 0.f;
+    if (job == kJobLambda) {
+        if (a.stage[j].tau == 0 || absent) return;      // nothing to tune, or no gradient arrived
+        // the two series: 0 and 1 when the state pass produced them, 3 and 4 when the one-pass step did
+        double total[2];
+        ordered_sums<2, kSumLanes>(a.partials + (size_t)(a.fused_lambda ? 3u : 0u) * a.n_chunks, a.n_chunks, c0, c1, red, total);
+        if (threadIdx.x == 0)
+            a.lambda_dev[j] = lambda_descent_step(a.lambda_dev[j], total[0], total[1], a.alpha, a.eta_lambda);
         return;
     }
-    const uint32_t c0 = a.stage[j].chunk_begin;
-    const uint32_t c1 = j + 1 < a.n_stages ? a.stage[j + 1].chunk_begin : a.n_chunks;
+    if (absent) {
+        if (threadIdx.x == 0) a.norms_out[j * 3 + job] = 0.f;
+        return;
+    }
     double total[1];
-    ordered_sums<1, kSumLanes>(a.partials + (size_t)k * a.n_chunks, a.n_chunks, c0, c1, red, total);
-    if (threadIdx.x == 0) a.norms_out[j * 3 + k] = (float)total[0];
+    ordered_sums<1, kSumLanes>(a.partials + (size_t)job * a.n_chunks, a.n_chunks, c0, c1, red, total);
+    if (threadIdx.x == 0) a.norms_out[j * 3 + job] = (float)total[0];
 }
 
 // ---- push: fp32 source -> ring slot (+ master) ----------------------------------------------------
@@ -937,42 +938,62 @@ __global__ void __launch_bounds__(kThreads) mix_kernel(char *dst, const char *sr
 }
 
 // ---- per-launch event timing of the step kernel ---------------------------------------------------
+// One profiling session per process at a time, owned by the thread that began it: only that thread's launches
+// are recorded (another thread stepping another plan meanwhile is left alone), and begin/end from two threads
+// cannot interleave.
 struct Profiler {
+    std::mutex mutex;
     std::vector<hipEvent_t> start, stop;
     int32_t used = 0;
     bool on = false;
+    std::thread::id owner;
 };
 static Profiler g_prof;
 
-int profile_begin(int32_t capacity) {
-    if (g_prof.on) return -1;
-    g_prof.start.assign(capacity, nullptr);
-    g_prof.stop.assign(capacity, nullptr);
-    for (int32_t i = 0; i < capacity; ++i) {
-        hipError_t e = hipEventCreate(&g_prof.start[i]);
-        if (e == hipSuccess) e = hipEventCreate(&g_prof.stop[i]);
-        if (e != hipSuccess) return (int)e;
-    }
-    g_prof.used = 0;
-    g_prof.on = true;
-    return 0;
-}
-
-int profile_end(float *ms_out, int32_t cap, int32_t *n_out) {
-    if (!g_prof.on) return -1;
-    hipError_t e = hipSuccess;
-    if (g_prof.used > 0) e = hipEventSynchronize(g_prof.stop[g_prof.used - 1]);
-    for (int32_t i = 0; i < g_prof.used && i < cap && e == hipSuccess; ++i)
-        e = hipEventElapsedTime(&ms_out[i], g_prof.start[i], g_prof.stop[i]);
-    *n_out = g_prof.used;
+static void profile_destroy_events() {
     for (size_t i = 0; i < g_prof.start.size(); ++i) {
         if (g_prof.start[i]) (void)hipEventDestroy(g_prof.start[i]);
         if (g_prof.stop[i]) (void)hipEventDestroy(g_prof.stop[i]);
     }
     g_prof.start.clear();
     g_prof.stop.clear();
+}
+
+int profile_begin(int32_t capacity) {
+    std::lock_guard<std::mutex> lock(g_prof.mutex);
+    if (g_prof.on) return -1;
+    g_prof.start.assign(capacity, nullptr);
+    g_prof.stop.assign(capacity, nullptr);
+    for (int32_t i = 0; i < capacity; ++i) {
+        hipError_t e = hipEventCreate(&g_prof.start[i]);
+        if (e == hipSuccess) e = hipEventCreate(&g_prof.stop[i]);
+        if (e != hipSuccess) { profile_destroy_events(); return (int)e; }      // nothing is left behind
+    }
+    g_prof.used = 0;
+    g_prof.owner = std::this_thread::get_id();
+    g_prof.on = true;
+    return 0;
+}
+
+int profile_end(float *ms_out, int32_t cap, int32_t *n_out) {
+    std::lock_guard<std::mutex> lock(g_prof.mutex);
+    if (!g_prof.on) return -1;
+    if (g_prof.owner != std::this_thread::get_id()) return -2;
+    hipError_t e = hipSuccess;
+    if (g_prof.used > 0) e = hipEventSynchronize(g_prof.stop[g_prof.used - 1]);
+    for (int32_t i = 0; i < g_prof.used && i < cap && e == hipSuccess; ++i)
+        e = hipEventElapsedTime(&ms_out[i], g_prof.start[i], g_prof.stop[i]);
+    *n_out = g_prof.used;
+    profile_destroy_events();
     g_prof.on = false;
     return (int)e;
+}
+
+// The event pair for the launch the calling thread is about to make, or -1 if none is to be recorded.
+static int32_t profile_claim() {
+    std::lock_guard<std::mutex> lock(g_prof.mutex);
+    if (!g_prof.on || g_prof.owner != std::this_thread::get_id() || g_prof.used >= (int32_t)g_prof.start.size()) return -1;
+    return g_prof.used++;
 }
 
 // ---- launchers ------------------------------------------------------------------------------------
@@ -1210,8 +1231,8 @@ int launch_step(const ferret_plan &plan, const StepArgs &args, void *stream) {
         streamed = need > streamed ? need : streamed;
     }
     const bool norms = a.norms_out != nullptr, gout = a.grad_out != nullptr;
-    const bool timed = g_prof.on && g_prof.used < (int32_t)g_prof.start.size();
-    if (timed) (void)hipEventRecord(g_prof.start[g_prof.used], st);
+    const int32_t timed = profile_claim();
+    if (timed >= 0) (void)hipEventRecord(g_prof.start[timed], st);
     StepLaunch l;
     l.persistent = grid < n_launch && !a.accum && !a.penalized && !a.fused_lambda;
     l.chunks = n_launch;
@@ -1226,15 +1247,12 @@ int launch_step(const ferret_plan &plan, const StepArgs &args, void *stream) {
                plan.cache_policy != 2 && (plan.cache_policy == 1 || working_set <= kCacheResidentBytes);
     hipError_t e = hipSuccess;
     if (n_launch > 0) e = plan.prec == FERRET_F32 ? launch_step_f32(a, l, st) : launch_step_bf16(a, l, st);
-    if (timed) (void)hipEventRecord(g_prof.stop[g_prof.used++], st);
+    if (timed >= 0) (void)hipEventRecord(g_prof.stop[timed], st);
     if (e != hipSuccess) return (int)e;
-    if (a.fused_lambda) {       // lambda takes its step for the next call
-        hipLaunchKernelGGL(lambda_step_kernel, dim3(a.n_stages), dim3(kSumLanes), 0, st, a);
-        e = hipGetLastError();
-        if (e != hipSuccess) return (int)e;
-    }
-    if (norms) {
-        hipLaunchKernelGGL(norms_finalize_kernel, dim3(a.n_stages, 3), dim3(kSumLanes), 0, st, a);
+    // the stages' sums: the three norms, and after a one-pass adaptive step lambda's step for the next call
+    const uint32_t first_job = norms ? 0u : kJobLambda, n_jobs = (norms ? 3u : 0u) + (a.fused_lambda ? 1u : 0u);
+    if (n_jobs > 0) {
+        hipLaunchKernelGGL(stage_sums_kernel, dim3(a.n_stages, n_jobs), dim3(kSumLanes), 0, st, a, first_job);
         e = hipGetLastError();
     }
     return (int)e;
@@ -1267,7 +1285,7 @@ int launch_lambda_update(const ferret_plan &plan, const StepArgs &args, void *st
     }
     hipError_t e = plan.prec == FERRET_F32 ? launch_state_f32(args, lds, st) : launch_state_bf16(args, lds, st);
     if (e != hipSuccess) return (int)e;
-    hipLaunchKernelGGL(lambda_step_kernel, dim3(args.n_stages), dim3(kSumLanes), 0, st, args);
+    hipLaunchKernelGGL(stage_sums_kernel, dim3(args.n_stages, 1), dim3(kSumLanes), 0, st, args, kJobLambda);
     return (int)hipGetLastError();
 }
 
