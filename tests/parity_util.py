@@ -30,6 +30,17 @@ from paper_2503_12053_amd import binding as B
 from paper_2503_12053_amd import workloads as W
 
 RTOL = 1e-5
+BIG = 50_000_000          # workloads beyond this many parameters: stages are generated and checked on a few host threads
+
+
+def map_stages(fn, n_stages, big):
+    """[fn(j) for j in range(n_stages)]; for big workloads on four host threads (the generator, the oracle and
+    numpy release the interpreter lock), in stage order either way."""
+    if not big or n_stages == 1:
+        return [fn(j) for j in range(n_stages)]
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(max_workers=4) as pool:
+        return list(pool.map(fn, range(n_stages)))
 
 
 def assert_close_f32(got, ref, what):
@@ -148,9 +159,11 @@ def load_workload(w: W.Workload, amplified=False, chunk_elems=0, tuning=None, he
                                ring_depth=ring_depth)
     st = B.DeviceState(plan, tensors_of(w), device=device)
     host, hd, valid = [], [], []
+    generated = map_stages(lambda j: W.generate_stage(w, j, amplified, n_versions=plan.stage_ring_depth(j)),
+                           w.n_stages, w.numel > BIG)
     for j in range(w.n_stages):
         R = plan.stage_ring_depth(j)
-        data = W.generate_stage(w, j, amplified, n_versions=R)
+        data = generated[j]
         h = st.load_versions(j, data.versions, None if heads is None else heads[j] % R)
         st.set_flat(st.grads, j, data.grads)
         if data.master is not None:
@@ -158,7 +171,7 @@ def load_workload(w: W.Workload, amplified=False, chunk_elems=0, tuning=None, he
         hd.append(h)
         valid.append(R)
         host.append(data)
-        if w.numel > 50_000_000:
+        if w.numel > BIG:
             print(f"  loaded stage {j} of {w.name}", flush=True)
     plan.set_state(hd, valid)
     return plan, st, host
@@ -183,7 +196,8 @@ def check_step_against_oracle(w, plan, st, host, K=None, lam=None, lr=None, n_th
     K = w.n_iters if K is None else K
     norms = st.norms.cpu().numpy().astype(np.float64)
     stats = {}
-    for j in range(w.n_stages):
+
+    def check_stage(j):
         tau = plan.stage_effective_staleness(j)
         ref = oracle_stage(w, host[j], tau, K, lam, lr, n_threads)
         slot = plan.stage_write_slot(j)
@@ -204,6 +218,8 @@ def check_step_against_oracle(w, plan, st, host, K=None, lam=None, lr=None, n_th
                                                         abs_slack=slack)
             assert_bf16_is_rounded_master(got_new, got_m, tag + " new version vs own master")
         np.testing.assert_allclose(norms[j], ref["norms"], rtol=RTOL, atol=1e-30, err_msg=tag + " norms")
-        if w.numel > 50_000_000:
+        if w.numel > BIG:
             print(f"  checked stage {j} of {w.name}", flush=True)
+
+    map_stages(check_stage, w.n_stages, w.numel > BIG)
     return stats

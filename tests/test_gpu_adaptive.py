@@ -22,11 +22,14 @@ def _gpu():
 def _state(w, st, seed, lam0):
     """Random non-trivial averages so that the first step already moves lambda."""
     st.enable_adaptive(lam0)
-    host = []
-    for j, n in enumerate(w.stage_numel()):
+
+    def draw(j):
         g = torch.Generator().manual_seed(seed * 100 + j)
-        vr = torch.randn(n, generator=g)
-        va = torch.randn(n, generator=g) * 0.05
+        n = w.stage_numel()[j]
+        return torch.randn(n, generator=g), torch.randn(n, generator=g) * 0.05
+
+    host = []
+    for j, (vr, va) in enumerate(PU.map_stages(draw, w.n_stages, w.numel > PU.BIG)):
         st.set_flat(st.v_r, j, vr)
         st.set_flat(st.v_a, j, va)
         host.append((vr.numpy().copy(), va.numpy().copy()))
@@ -36,9 +39,9 @@ def _state(w, st, seed, lam0):
 def _check(w, plan, st, host, state, lams, alpha, eta_l, K, tag, fused=False, n_threads=1):
     norms = st.norms.cpu().numpy().astype(np.float64)
     lam_gpu = st.lambda_dev.cpu().numpy()
-    new_state, new_lams = [], []
     bf16 = w.precision == "bf16"
-    for j in range(w.n_stages):
+
+    def check_stage(j):
         tau = plan.stage_effective_staleness(j)
         d = host[j]
         window = d.versions[len(d.versions) - 1 - tau:]
@@ -68,9 +71,10 @@ def _check(w, plan, st, host, state, lams, alpha, eta_l, K, tag, fused=False, n_
         else:
             PU.assert_close_f32(st.get_version(j, slot).numpy(), ref["new"], t + " version")
         np.testing.assert_allclose(norms[j], ref["norms"], rtol=PU.RTOL, atol=1e-30, err_msg=t + " norms")
-        new_state.append((got_r.copy(), got_a.copy()))
-        new_lams.append(float(lam_gpu[j]))
-    return new_state, new_lams
+        return (got_r.copy(), got_a.copy()), float(lam_gpu[j])
+
+    results = PU.map_stages(check_stage, w.n_stages, w.numel > PU.BIG)
+    return [r[0] for r in results], [r[1] for r in results]
 
 
 @pytest.mark.parametrize("fused", [False, True])

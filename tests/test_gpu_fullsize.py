@@ -176,8 +176,9 @@ def test_mixed_350m_one_iteration_per_version_step_amplified(mixed_nominal):
     st = L.state_for(plan)
     L.host.clear()
     host = []
+    generated = PU.map_stages(lambda j: W.generate_stage(w, j, True, n_versions=w.ring_depth), w.n_stages, True)
     for j in range(w.n_stages):
-        d = W.generate_stage(w, j, True, n_versions=w.ring_depth)
+        d = generated[j]
         assert st.load_versions(j, d.versions, L.heads[j]) == L.heads[j]
         st.set_flat(st.grads, j, d.grads)
         st.set_flat(st.master, j, d.master)
