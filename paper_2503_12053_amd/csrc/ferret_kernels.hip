@@ -10,13 +10,16 @@
 //                                                 round-to-nearest-even to bf16)
 //
 // Design for the machine (every choice below was measured on MI355X):
-//   * every operand is touched exactly once, with 128-bit (fp32) / 64-bit (bf16) non-temporal
-//     accesses; consecutive lanes of a 64-wide wavefront touch consecutive vectors, so every
-//     access of a wavefront is one contiguous run of memory;
-//   * one workgroup of 256 lanes per chunk of 2048 elements (two vectors per lane, one after the
-//     other): all loads of a vector (gradient + K'+1 versions) are issued before the first
-//     arithmetic, and the hardware dispatcher balances the load; a cap on resident workgroups per
-//     CU (unused LDS) keeps the traffic in flight at the measured optimum for large steps;
+//   * every operand is touched exactly once, with 128-bit (fp32) / 64-bit (bf16) accesses --
+//     non-temporal for plans that stream, ordinary cached ones for plans small enough to stay in
+//     the memory-side cache from step to step; consecutive lanes of a 64-wide wavefront touch
+//     consecutive vectors, so every access of a wavefront is one contiguous run of memory;
+//   * one workgroup of 256 lanes per chunk, vectors one after the other: all loads of a vector
+//     (gradient + K'+1 versions) are issued before the first arithmetic, and the hardware
+//     dispatcher balances the load.  A stage's chunk size is chosen by the plan so that every
+//     workgroup moves about the same bytes whatever its stage's K' (2048 elements at K' = 3 in
+//     fp32, more for shallower stages, fewer for deeper ones); a cap on resident workgroups per CU
+//     (unused LDS) then keeps the traffic in flight at the measured optimum for large steps;
 //   * a stage's tensors are one flat bucket; the stage table (48 B per stage) arrives as a kernel
 //     argument; the chunk id is the block index, so the stage is found with scalar loads and all
 //     stream base addresses live in SGPRs (lanes add a 32-bit offset).  A persistent grid-stride

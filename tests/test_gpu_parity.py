@@ -603,3 +603,39 @@ def test_stage_beyond_four_gibibytes_sampled(precision):
     for s in (1, 2):
         for (a, b), vs in zip(windows, before):
             assert torch.equal(ring[off[s] + a: off[s] + b].cpu(), vs[s])
+
+
+# ---- per-launch timing sessions ------------------------------------------------------------------------
+def test_profile_session_belongs_to_the_thread_that_began_it():
+    """Only the owner's launches are recorded; another thread can neither begin a second session nor end this one."""
+    import threading
+    w = W.custom_workload("prof", [[50_000], [20_000]], [1, 0], 2, 1, seed=88)
+    plan, st, _ = PU.load_workload(w, amplified=True)
+    torch.cuda.synchronize()
+    B.ferret_profile_begin(8)
+    other = {}
+
+    def intruder():
+        try:
+            B.ferret_profile_begin(4)
+        except B.FerretError as e:
+            other["begin"] = e.status
+        plan2, st2, _ = PU.load_workload(w, amplified=True)
+        st2.step(w.lam, w.lr)                       # a launch from another thread: not recorded
+        torch.cuda.synchronize()
+        try:
+            B.ferret_profile_end(8)
+        except B.FerretError as e:
+            other["end"] = e.status
+
+    t = threading.Thread(target=intruder)
+    t.start()
+    t.join()
+    assert other == {"begin": B.FERRET_ESTATE, "end": B.FERRET_ESTATE}
+    for _ in range(3):
+        st.step(w.lam, w.lr)
+    ms = B.ferret_profile_end(8)
+    assert len(ms) == 3 and all(0.0 < x < 50.0 for x in ms)
+    with pytest.raises(B.FerretError) as e:
+        B.ferret_profile_end(8)
+    assert e.value.status == B.FERRET_ESTATE
