@@ -168,6 +168,13 @@ __device__ __forceinline__ float approximator(float g, float lambda, float v_new
     return fmaf(lambda * g * g, v_new - v_old, g);
 }
 
+// Ring slot arithmetic without divisions (all values wave-uniform; the host guarantees head < R and tau < R):
+// x mod R for x < 2R, and the slot of the oldest version read, (head - tau) mod R.
+__device__ __forceinline__ uint32_t wrap(uint32_t x, uint32_t R) { return x >= R ? x - R : x; }
+__device__ __forceinline__ uint32_t oldest_slot(uint32_t head, uint32_t tau, uint32_t R) {
+    return head >= tau ? head - tau : head + R - tau;
+}
+
 // Everything a lane needs to know about the chunk it works on.  All pointers are wave-uniform
 // (they live in scalar registers); lanes add a 32-bit byte offset, which is the addressing form
 // the global load/store instructions take directly.
@@ -419,7 +426,10 @@ __device__ __forceinline__ void run_chunk_streamed(const ChunkPtrs<1> &p, const 
     using Raw = typename S::Raw;
     constexpr int E = S::kElems;
     constexpr uint32_t RB = S::kRawBytes;
-    const uint32_t oldest = (head + R - tau) % R;
+    const uint32_t oldest = oldest_slot(head, tau, R);
+    // boundary s_i = floor(i tau / K') advances by tau div K' per iteration plus a carry from the remainders:
+    // one division per chunk instead of one per boundary
+    const uint32_t step_q = tau / kp, step_r = tau - step_q * kp;
     for (uint32_t vec = threadIdx.x; vec < n_vecs; vec += kThreads) {
         float g[E], prev[E], cur[E], first[E];
         v4f m[S::kF4], ac[S::kF4];
@@ -440,14 +450,20 @@ __device__ __forceinline__ void run_chunk_streamed(const ChunkPtrs<1> &p, const 
         }
         // Batches of kStreamBatch boundaries, two register sets used in turn: the loads of the next batch are
         // issued before the iterations of the current one, so memory latency overlaps across batches.
+        // batches are loaded in the order of their boundaries, so the running boundary (its slot and the
+        // remainder of i tau / K') is carried from one batch to the next
+        uint32_t slot = oldest, rem = 0;
         auto load_batch = [&](uint32_t i, Raw (&r)[kStreamBatch]) {
             const uint32_t count = kp - i + 1 < (uint32_t)kStreamBatch ? kp - i + 1 : (uint32_t)kStreamBatch;   // uniform
 #pragma unroll
             for (int b = 0; b < kStreamBatch; ++b) {
                 if ((uint32_t)b >= count) break;
-                const uint32_t s_i = (uint32_t)(((uint64_t)(i + b) * tau) / kp);
+                rem += step_r;                                        // boundary i + b from boundary i + b - 1
+                const uint32_t carry = rem >= kp ? 1u : 0u;
+                rem -= carry ? kp : 0u;
+                slot = wrap(slot + step_q + carry, R);
                 if ((OUT & 4) != 0 && S::kMaster && i + b == kp) r[b] = newest_from_master<S>(m);
-                else r[b] = ld_off<S::kNT, Raw>(arena + (uint64_t)((oldest + s_i) % R) * slot_bytes, vec * RB);
+                else r[b] = ld_off<S::kNT, Raw>(arena + (uint64_t)slot * slot_bytes, vec * RB);
             }
         };
         auto iterate_batch = [&](uint32_t i, const Raw (&r)[kStreamBatch]) {
@@ -597,15 +613,16 @@ __device__ __forceinline__ void do_chunk(const StepArgs &a, const ChunkInfo &c, 
     constexpr uint64_t kStoreBytes = S::kStoreBytes;
     ChunkPtrs<NV> p;
     p.g = static_cast<const char *>(a.grads) + c.flat_elem0 * kStoreBytes;
-    const uint32_t oldest = (c.head + c.R - c.tau) % c.R;
+    const uint32_t oldest = oldest_slot(c.head, c.tau, c.R);
     constexpr uint32_t kp = NV - 1;
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
-        // NV == 1: only V[tau].  Otherwise boundary s_i = floor(i*tau/K') of the K' = NV-1 segments.
-        const uint32_t s_i = NV == 1 ? c.tau : (uint32_t)(((uint64_t)i * c.tau) / (kp ? kp : 1));
-        p.v[i] = c.arena + (uint64_t)((oldest + s_i) % c.R) * c.slot_bytes;
+        // NV == 1: only V[tau].  Otherwise boundary s_i = floor(i*tau/K') of the K' = NV-1 segments (a division by
+        // a compile-time constant; i*tau stays far below 2^32).
+        const uint32_t s_i = NV == 1 ? c.tau : ((uint32_t)i * c.tau) / (kp ? kp : 1u);
+        p.v[i] = c.arena + (uint64_t)wrap(oldest + s_i, c.R) * c.slot_bytes;
     }
-    p.out = const_cast<char *>(c.arena) + (uint64_t)((c.head + 1) % c.R) * c.slot_bytes;
+    p.out = const_cast<char *>(c.arena) + (uint64_t)wrap(c.head + 1u, c.R) * c.slot_bytes;
     p.master = a.master ? reinterpret_cast<char *>(a.master) + c.flat_elem0 * 4 : nullptr;
     p.g_out = (OUT & 1) ? reinterpret_cast<char *>(a.grad_out) + c.flat_elem0 * 4 : nullptr;
     p.accum = (OUT & 2) ? reinterpret_cast<char *>(a.accum) + c.flat_elem0 * 4 : nullptr;
@@ -613,7 +630,7 @@ __device__ __forceinline__ void do_chunk(const StepArgs &a, const ChunkInfo &c, 
     p.acc_update = c.acc_update;
     p.pen_scale = (OUT & 8) ? a.pen_scale[c.stage] : 1.f;
     p.pen_inv_c = (OUT & 8) ? a.pen_inv_c[c.stage] : 0.f;
-    p.v1 = (OUT & 16) ? c.arena + (uint64_t)((oldest + 1) % c.R) * c.slot_bytes : nullptr;
+    p.v1 = (OUT & 16) ? c.arena + (uint64_t)wrap(oldest + 1u, c.R) * c.slot_bytes : nullptr;
     p.v_r = (OUT & 16) ? reinterpret_cast<char *>(a.v_r) + c.flat_elem0 * 4 : nullptr;
     p.v_a = (OUT & 16) ? reinterpret_cast<char *>(a.v_a) + c.flat_elem0 * 4 : nullptr;
     p.alpha = a.alpha;
@@ -664,7 +681,7 @@ __device__ __forceinline__ void process_chunk(const StepArgs &a, const ChunkInfo
         ChunkPtrs<1> p;
         p.g = static_cast<const char *>(a.grads) + c.flat_elem0 * kStoreBytes;
         p.v[0] = nullptr;
-        p.out = const_cast<char *>(c.arena) + (uint64_t)((c.head + 1) % c.R) * c.slot_bytes;
+        p.out = const_cast<char *>(c.arena) + (uint64_t)wrap(c.head + 1u, c.R) * c.slot_bytes;
         p.master = a.master ? reinterpret_cast<char *>(a.master) + c.flat_elem0 * 4 : nullptr;
         p.g_out = (OUT & 1) ? reinterpret_cast<char *>(a.grad_out) + c.flat_elem0 * 4 : nullptr;
         p.accum = (OUT & 2) ? reinterpret_cast<char *>(a.accum) + c.flat_elem0 * 4 : nullptr;
@@ -672,7 +689,7 @@ __device__ __forceinline__ void process_chunk(const StepArgs &a, const ChunkInfo
         p.acc_update = c.acc_update;
         p.pen_scale = 1.f;
         p.pen_inv_c = 0.f;
-        p.v1 = (OUT & 16) ? c.arena + (uint64_t)((c.head + c.R - c.tau + 1) % c.R) * c.slot_bytes : nullptr;
+        p.v1 = (OUT & 16) ? c.arena + (uint64_t)wrap(oldest_slot(c.head, c.tau, c.R) + 1u, c.R) * c.slot_bytes : nullptr;
         p.v_r = (OUT & 16) ? reinterpret_cast<char *>(a.v_r) + c.flat_elem0 * 4 : nullptr;
         p.v_a = (OUT & 16) ? reinterpret_cast<char *>(a.v_a) + c.flat_elem0 * 4 : nullptr;
         p.alpha = a.alpha;
@@ -766,10 +783,10 @@ __global__ void __launch_bounds__(kThreads) lambda_state_kernel(const StepArgs a
     if (c.tau == 0 || c.skip) return;       // uniform over the workgroup: nothing to tune, or no gradient arrived
     float acc0 = 0.f, acc1 = 0.f;
     {
-        const uint32_t oldest = (c.head + c.R - c.tau) % c.R;
+        const uint32_t oldest = oldest_slot(c.head, c.tau, c.R);
         const char *g_ptr = static_cast<const char *>(a.grads) + c.flat_elem0 * S::kStoreBytes;
         const char *v0 = c.arena + (uint64_t)oldest * c.slot_bytes;
-        const char *v1 = c.arena + (uint64_t)((oldest + 1) % c.R) * c.slot_bytes;
+        const char *v1 = c.arena + (uint64_t)wrap(oldest + 1u, c.R) * c.slot_bytes;
         char *vr_ptr = reinterpret_cast<char *>(a.v_r) + c.flat_elem0 * 4;
         char *va_ptr = reinterpret_cast<char *>(a.v_a) + c.flat_elem0 * 4;
         const float alpha = a.alpha, beta = 1.0f - a.alpha;
