@@ -1044,7 +1044,7 @@ static uint32_t grid_for(const ferret_plan &plan, uint32_t n_chunks, int *err) {
 
 // Resident-workgroup cap.  Measured on MI355X: for steps that stream far more than the 256 MB
 // memory-side cache holds, throughput depends on how many workgroups a CU holds at once, with a sharp
-// optimum that moves with the traffic of one chunk: at the default 2048-element chunks of fp32 the best
+// optimum that moves with the traffic of one chunk: with 2048-element chunks of fp32 in every stage the best
 // count is 5 for K' = 0 (4 when the weight gap is read as well), 4 for K' = 1, 3 for K' = 2..4, 2 beyond
 // (and 3 for bf16 at K' = 4); one too few costs 5-10 %, one too many 2-5 %.  ceil(120 KiB / bytes one
 // chunk moves) reproduces those counts.  The launch enforces the count by reserving LDS the kernel never

@@ -19,6 +19,10 @@ def _lib():
 stage_lists = st.lists(st.lists(st.integers(1, 5000), min_size=1, max_size=4), min_size=1, max_size=6)
 
 
+def elt_of(prec):
+    return 4 if prec == B.FERRET_F32 else 2
+
+
 @settings(max_examples=60, deadline=None, derandomize=True)
 @given(sizes=stage_lists, data=st.data())
 def test_layout_and_state_invariants(sizes, data):
@@ -29,8 +33,21 @@ def test_layout_and_state_invariants(sizes, data):
     prec = data.draw(st.sampled_from([B.FERRET_F32, B.FERRET_BF16_MASTER_F32]))
     minimal = data.draw(st.booleans())
     chunk = data.draw(st.sampled_from([0, 1024, 4096]))
+    tuning = data.draw(st.sampled_from([None, dict(cache_policy=1), dict(cache_policy=2, resident_cap=3),
+                                        dict(chunk_bytes=1), dict(chunk_bytes=30_000), dict(chunk_bytes=1 << 22),
+                                        dict(slot_align_elems=512, slot_skew_elems=24, blocks_per_cu=2)]))
+    if tuning and "chunk_bytes" in tuning:
+        chunk = 0
     tensors = [(n, j) for j, ss in enumerate(sizes) for n in ss]
-    plan = B.ferret_plan_buckets(tensors, P, tau, K, B.FERRET_RING_DEPTH_MINIMAL if minimal else R, prec, chunk)
+    plan = B.ferret_plan_buckets(tensors, P, tau, K, B.FERRET_RING_DEPTH_MINIMAL if minimal else R, prec, chunk, tuning)
+    if tuning and "chunk_bytes" in tuning:
+        # the byte target picks the multiple of 1024 elements nearest to target / (bytes per element in flight)
+        for j in range(P):
+            kp = tau[j] if K < 0 else min(K, tau[j])
+            per = elt_of(prec) * (min(kp + 1, 9) if kp <= 8 else 8) + 2 * elt_of(prec) + (0 if prec == B.FERRET_F32 else 8)
+            per += elt_of(prec) if kp == 0 and tau[j] > 0 else 0
+            want = max(1, (tuning["chunk_bytes"] + per * 512) // (per * 1024)) * 1024
+            assert plan.stage_chunk_elems(j) == min(want, 1 << 24), (j, kp, per)
     elt = 4 if prec == B.FERRET_F32 else 2
     # regions: disjoint, ordered, inside the totals
     ring, flat, i = [], [], 0
