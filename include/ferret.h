@@ -252,7 +252,9 @@ ferret_status ferret_compensate_step_noalloc(const ferret_plan *plan, void *ring
 /* The same step for some of the plan's stages only (in a pipeline the gradients of different stages
  * arrive at different times): stage j takes part iff active[j] != 0 (host int32[n_stages]).  Stages
  * left out are not read or written, their norms_out rows read 0, and they have nothing to commit.
- * For the stages that take part the result is bit-identical to ferret_compensate_step. */
+ * For the stages that take part the result is bit-identical to ferret_compensate_step.  Only the stages that take
+ * part need to hold a version (FERRET_ESTATE otherwise); the same holds for the mode array of the accumulating
+ * steps and the active array of the adaptive one. */
 ferret_status ferret_compensate_stages(const ferret_plan *plan, void *ring, const void *grads, float *master,
                                        const int32_t *active, float lambda, float lr, float *norms_out,
                                        void *grad_out, void *workspace, void *hip_stream);

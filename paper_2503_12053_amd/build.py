@@ -10,6 +10,7 @@ from __future__ import annotations
 
 import hashlib
 import os
+import re
 import shutil
 import subprocess
 import sys
@@ -40,15 +41,26 @@ FLAGS = [f"--offload-arch={ARCH}", "-O3", "-std=c++17", "-fPIC",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 
+_TOKEN = re.compile(r'''"(?:\\.|[^"\\])*"|'(?:\\.|[^'\\])*'|//[^\n]*|/\*.*?\*/''', re.S)
+
+
+def _code_only(text: str) -> str:
+    """The source text without comments and with runs of white space collapsed (string and character literals are
+    kept as they are): what the compiler sees, so that editing a comment does not change the hash below."""
+    text = _TOKEN.sub(lambda m: m.group(0) if m.group(0)[0] in "\"'" else " ", text)
+    return " ".join(text.split())
+
+
 def source_hash() -> str:
-    """First 12 hex digits of the SHA-256 over every source and header the library is built from (in a fixed
-    order) and the compiler flags.  The library reports it through ferret_version(), so that a measurement can
-    say which sources it belongs to and a stored profile summary can be matched against the build that is timed."""
+    """First 12 hex digits of the SHA-256 over the code (comments stripped) of every source and header the library
+    is built from, in a fixed order, and the compiler flags.  The library reports it through ferret_version(), so
+    that a measurement can say which sources it belongs to and a stored profile summary can be matched against the
+    build that is timed."""
     h = hashlib.sha256()
     for path in sorted(SOURCES + HEADERS):
         h.update(os.path.basename(path).encode() + b"\0")
-        with open(path, "rb") as f:
-            h.update(f.read())
+        with open(path, "r", encoding="utf-8") as f:
+            h.update(_code_only(f.read()).encode())
     h.update(" ".join(f for f in FLAGS if not f.startswith("/") and os.sep not in f).encode())
     return h.hexdigest()[:12]
 

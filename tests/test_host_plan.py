@@ -38,6 +38,16 @@ def _plan(sizes_per_stage, tau, K=-1, R=None, prec=B.FERRET_F32, chunk=0, tuning
     return B.ferret_plan_buckets(tensors, len(sizes_per_stage), tau, K, R, prec, chunk, tuning), tensors
 
 
+def test_library_reports_the_hash_of_the_sources_in_the_tree(lib):
+    """ferret_version() ends with the hash of the code the library was built from; it must be the hash of the sources
+    in this tree (a stale library fails here), and comments or white space do not change it."""
+    from paper_2503_12053_amd import build
+    assert lib.ferret_version().decode().split()[-1] == build.source_hash()
+    code = 'int a = 1; const char *s = "// kept /* kept */"; char c = \'"\';'
+    commented = 'int a = 1;   // the stage\'s "count"\n/* more\n "text" */ const char *s = "// kept /* kept */";\tchar c = \'"\';'
+    assert build._code_only(commented) == build._code_only(code) == code
+
+
 def test_layout_alignment_and_disjointness(lib):
     sizes = [[1, 3, 1001, 64], [7], [4096, 5]]
     plan, tensors = _plan(sizes, [2, 1, 0], R=3)
