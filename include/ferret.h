@@ -106,7 +106,13 @@ typedef struct {
                                   with ordinary cached accesses, everything else with non-temporal ones;
                                   1: cached wherever that variant exists; 2: always non-temporal.  Results are
                                   bit-identical either way. */
-    int32_t reserved[2];       /* must be 0 */
+    int32_t xcd_group;         /* how the chunks of a launch are dealt to the GPU's 8 XCDs (workgroups go to them
+                                  round-robin): 1: every XCD takes every eighth chunk; N > 1: every XCD takes runs of N
+                                  consecutive chunks, i.e. a contiguous stretch of every stream; 0: 16 for fp32 plans
+                                  that stream and whose median stage iterates at least three times (measured 2-3 %
+                                  faster there), 1 otherwise (where grouping measured 1-3 % slower).  Results are
+                                  bit-identical for any value. */
+    int32_t reserved;          /* must be 0 */
 } ferret_tuning;
 
 typedef struct ferret_plan ferret_plan;   /* opaque; host memory; owned by the caller via destroy */

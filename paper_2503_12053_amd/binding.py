@@ -40,7 +40,7 @@ class ferret_tensor(ctypes.Structure):
 class ferret_tuning(ctypes.Structure):
     _fields_ = [("slot_align_elems", c_int64), ("slot_skew_elems", c_int64), ("chunk_bytes", c_int64),
                 ("blocks_per_cu", c_int32), ("resident_cap", c_int32), ("newest_from_master", c_int32),
-                ("cache_policy", c_int32), ("reserved", c_int32 * 2)]
+                ("cache_policy", c_int32), ("xcd_group", c_int32), ("reserved", c_int32)]
 
 
 class ferret_adaptive(ctypes.Structure):
@@ -214,7 +214,7 @@ def ferret_plan_buckets(tensors: Sequence, n_stages: int, staleness: Sequence[in
                            int(tuning.get("chunk_bytes", 0)),
                            int(tuning.get("blocks_per_cu", 0)), int(tuning.get("resident_cap", 0)),
                            int(tuning.get("newest_from_master", 0)), int(tuning.get("cache_policy", 0)),
-                           (c_int32 * 2)(int(tuning.get("reserved", 0)), 0))
+                           int(tuning.get("xcd_group", 0)), int(tuning.get("reserved", 0)))
         rc = lib.ferret_plan_buckets_tuned(arr, len(tensors), n_stages, st, n_iters, ring_depth, prec,
                                            chunk_elems, byref(tn), byref(out))
     _check(rc)

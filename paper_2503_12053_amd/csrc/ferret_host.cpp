@@ -106,9 +106,11 @@ ferret_status ferret_plan_buckets_tuned(const ferret_tensor *tensors, int32_t n_
         return FERRET_EINVAL;
     }
     int64_t slot_align = kDefaultSlotAlign, slot_skew = 0, chunk_bytes = 0;
-    int32_t blocks_per_cu = 0, resident_cap = 0, newest_from_master = 0, cache_policy = 0;
+    int32_t blocks_per_cu = 0, resident_cap = 0, newest_from_master = 0, cache_policy = 0, xcd_group = 0;
     if (tuning) {
-        if (tuning->reserved[0] != 0 || tuning->reserved[1] != 0) { set_error("plan: tuning.reserved must be 0"); return FERRET_EINVAL; }
+        if (tuning->reserved != 0) { set_error("plan: tuning.reserved must be 0"); return FERRET_EINVAL; }
+        xcd_group = tuning->xcd_group;
+        if (xcd_group < 0 || xcd_group > 4096) { set_error("plan: xcd_group = %d, need 0..4096", xcd_group); return FERRET_EINVAL; }
         chunk_bytes = tuning->chunk_bytes;
         if (chunk_bytes < 0 || chunk_bytes > (int64_t(1) << 30)) {
             set_error("plan: chunk_bytes = %lld, need 0 .. 2^30", (long long)chunk_bytes); return FERRET_EINVAL;
@@ -172,6 +174,7 @@ ferret_status ferret_plan_buckets_tuned(const ferret_tensor *tensors, int32_t n_
     p->n_iters = n_iters;
     p->chunk_elems = chunk_elems;
     p->cache_policy = cache_policy;
+    p->xcd_group = xcd_group;
     p->blocks_per_cu = blocks_per_cu;
     p->resident_cap = resident_cap;
     p->newest_from_master = newest_from_master;

@@ -51,7 +51,7 @@ struct StepArgs {
     float lr;
     uint32_t n_stages;
     uint32_t n_chunks;
-    uint32_t pad0_;
+    uint32_t xcd_group;      // > 1: consecutive chunks each XCD works on (set by the launcher)
     uint32_t fused_lambda;   // 1: the step kernel also runs the "update lambda" block (series 3, 4 of partials)
     // self-tuned lambda (null / zero for the fixed-lambda step)
     float *lambda_dev;   // float[n_stages]; when set, stage j uses lambda_dev[j] instead of `lambda`
@@ -122,6 +122,7 @@ struct ferret_plan {
     int32_t resident_cap = 0;
     int32_t newest_from_master = 0;   // bf16: recompute V[tau] from the master instead of reading it
     int32_t cache_policy = 0;         // 0: by working-set size, 1: cached accesses where available, 2: non-temporal
+    int32_t xcd_group = 0;            // 0: by storage type and K', 1: none, > 1: that many consecutive chunks per XCD
 };
 
 namespace ferret {

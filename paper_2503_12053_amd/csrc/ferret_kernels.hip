@@ -744,7 +744,16 @@ __global__ void __launch_bounds__(kThreads) step_kernel(const StepArgs a) {
             if (NORMS) __syncthreads();     // lds.red is reused by the next chunk
         }
     } else {
-        const uint32_t chunk = a.chunk_base + blockIdx.x;
+        // Workgroups are dealt to the 8 XCDs round-robin in the order of their ids.  With xcd_group = G > 1 the
+        // block index is permuted inside every full run of 8 G chunks so that each XCD works on G consecutive
+        // chunks (a contiguous run of every stream) instead of every eighth chunk; a last partial run keeps the
+        // identity.  A bijection on the launch's chunks, so results cannot depend on it.
+        uint32_t chunk = a.chunk_base + blockIdx.x;
+        if (a.xcd_group > 1u) {
+            const uint32_t G = a.xcd_group, span = 8u * G, n = a.chunk_end - a.chunk_base, b = blockIdx.x;
+            const uint32_t g = b / span, within = b - g * span;
+            if ((g + 1u) * span <= n) chunk = a.chunk_base + g * span + (within & 7u) * G + (within >> 3);
+        }
         // stage = number of stages (beyond the first) that begin at or before this chunk;
         // unused table entries hold UINT32_MAX and never count
         uint32_t stage = 0;
@@ -1068,9 +1077,12 @@ static uint32_t dyn_lds_for_cap(int32_t cap, uint32_t static_bytes) {
 constexpr uint64_t kInFlightTargetBytes = 120u * 1024u;
 constexpr uint64_t kStateTargetBytes = 100u * 1024u;     // the same for lambda_state_kernel
 
-static uint32_t reserve_lds_for_cap(const ferret_plan &plan, const StepArgs &a, bool persistent) {
+// Also reports, for launches that stream (traffic far beyond the memory-side cache), the K' of the stage at the
+// traffic-weighted median (-1 for launches that do not stream).
+static uint32_t reserve_lds_for_cap(const ferret_plan &plan, const StepArgs &a, bool persistent, int32_t *median_kp) {
     int32_t cap = plan.resident_cap;
-    if (cap == 0) {
+    *median_kp = -1;
+    {
         // default: cap only steps whose traffic is far beyond the memory-side cache; steps that run out
         // of that cache are latency-bound instead and want every wave they can get
         // Bytes one chunk of each stage moves; the cap is taken from the stage at the traffic-weighted median,
@@ -1078,7 +1090,7 @@ static uint32_t reserve_lds_for_cap(const ferret_plan &plan, const StepArgs &a, 
         const uint64_t sb = plan.prec == FERRET_F32 ? 4 : 2;
         uint64_t total = 0;
         uint64_t block[FERRET_MAX_STAGES], traffic[FERRET_MAX_STAGES];
-        uint32_t order[FERRET_MAX_STAGES], n = 0;
+        uint32_t order[FERRET_MAX_STAGES], kps[FERRET_MAX_STAGES], n = 0;
         for (uint32_t j = 0; j < a.n_stages; ++j) {
             if ((a.accum || a.masked) && a.mode[j] == 0) continue;
             const uint32_t kp = a.stage[j].kp;
@@ -1092,10 +1104,11 @@ static uint32_t reserve_lds_for_cap(const ferret_plan &plan, const StepArgs &a, 
             traffic[n] = a.stage[j].n_elems * (sb * (kp + 3u) + (plan.prec == FERRET_F32 ? 0u : 8u) +
                                                (a.fused_lambda && a.stage[j].tau > 0 ? sb + 16u : 0u));
             total += traffic[n];
+            kps[n] = kp;
             order[n] = n;
             ++n;
         }
-        if (total <= kCapThresholdBytes || n == 0) return 0;
+        if (total <= kCapThresholdBytes || n == 0) return cap > 0 ? dyn_lds_for_cap(cap, (persistent ? (uint32_t)sizeof(StageDesc) * FERRET_MAX_STAGES : 0u) + (uint32_t)sizeof(StepLds)) : 0;
         for (uint32_t i = 1; i < n; ++i)                      // insertion sort by bytes per chunk
             for (uint32_t k = i; k > 0 && block[order[k]] < block[order[k - 1]]; --k) {
                 const uint32_t t = order[k]; order[k] = order[k - 1]; order[k - 1] = t;
@@ -1105,10 +1118,19 @@ static uint32_t reserve_lds_for_cap(const ferret_plan &plan, const StepArgs &a, 
             seen += traffic[order[i]];
             if (2 * seen >= total) { block_bytes = block[order[i]]; break; }
         }
-        cap = (int32_t)((kInFlightTargetBytes + block_bytes - 1) / block_bytes);
-        if (cap < 2) cap = 2;
-        if (cap >= 8) return 0;                               // 8 fit anyway
+        // the traffic-weighted median of K' itself: the smallest k with at least half the traffic in stages of K' <= k
+        for (uint32_t k = 0; *median_kp < 0; ++k) {
+            uint64_t upto = 0;
+            for (uint32_t i = 0; i < n; ++i) upto += kps[i] <= k ? traffic[i] : 0u;
+            if (2 * upto >= total) *median_kp = (int32_t)k;
+        }
+        if (cap == 0) {
+            cap = (int32_t)((kInFlightTargetBytes + block_bytes - 1) / block_bytes);
+            if (cap < 2) cap = 2;
+            if (cap >= 8) return 0;                           // 8 fit anyway
+        }
     }
+    if (cap <= 0) return 0;
     // what step_kernel declares itself: the reduction buffers, and the stage table of the persistent variant
     const uint32_t used = (persistent ? (uint32_t)sizeof(StageDesc) * FERRET_MAX_STAGES : 0u) + (uint32_t)sizeof(StepLds);
     return dyn_lds_for_cap(cap, used);
@@ -1244,7 +1266,7 @@ int launch_step(const ferret_plan &plan, const StepArgs &args, void *stream) {
     const uint32_t grid = grid_for(plan, n_launch, &err);
     if (err) return err;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const StepArgs &a = args;
+    StepArgs a = args;
     int streamed = 0;    // kernel level: which K' the launch has to cover
     for (uint32_t j = 0; j < a.n_stages; ++j) {
         const int need = a.stage[j].kp <= kUnrolledItersSmall ? 0 : (a.stage[j].kp <= kUnrolledItersMid ? 1 : 2);
@@ -1261,7 +1283,16 @@ int launch_step(const ferret_plan &plan, const StepArgs &args, void *stream) {
     l.elide = plan.newest_from_master != 0;
     l.level = streamed;
     l.grid = l.persistent ? grid : n_launch;
-    l.lds = reserve_lds_for_cap(plan, a, l.persistent);
+    int32_t median_kp = -1;
+    l.lds = reserve_lds_for_cap(plan, a, l.persistent, &median_kp);
+    // XCD grouping (measured on MI355X at the resident caps above, step_kernel us without -> with 16 chunks per XCD):
+    // fp32, K' = 3: 306 -> 299; K' = 4: 355 -> 347; one iteration per version step (K' 7..0): 400 -> 395; accumulation
+    // 396 -> 388; 350 M parameters as fp32, K' = 4: 1528 -> 1487; but K' <= 2: 256 -> 257, 213 -> 214; with the lambda block
+    // fused in 530 -> 534; bf16 storage 1132 -> 1166.  Group sizes of 14..24 are equivalent, 2..8 and beyond 32 lose.
+    // So: fp32 launches that stream and whose median stage has K' >= 3 group 16 chunks per XCD, everything else none.
+    a.xcd_group = l.persistent ? 1u
+                  : plan.xcd_group > 0 ? (uint32_t)plan.xcd_group
+                  : (plan.prec == FERRET_F32 && median_kp >= 3 && !a.fused_lambda) ? 16u : 1u;
     const uint64_t working_set = working_set_bytes(plan.prec, plan.ring_elems, plan.flat_elems);
     l.cached = !l.persistent && streamed == 0 && !a.accum && !a.penalized && !a.fused_lambda && !a.lambda_dev && !l.elide &&
                plan.cache_policy != 2 && (plan.cache_policy == 1 || working_set <= kCacheResidentBytes);

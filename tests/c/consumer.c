@@ -29,7 +29,7 @@ int main(void) {
     SIZE(ferret_tuning);
     FIELD(ferret_tuning, slot_align_elems); FIELD(ferret_tuning, slot_skew_elems); FIELD(ferret_tuning, chunk_bytes);
     FIELD(ferret_tuning, blocks_per_cu); FIELD(ferret_tuning, resident_cap); FIELD(ferret_tuning, newest_from_master);
-    FIELD(ferret_tuning, cache_policy); FIELD(ferret_tuning, reserved);
+    FIELD(ferret_tuning, cache_policy); FIELD(ferret_tuning, xcd_group); FIELD(ferret_tuning, reserved);
     SIZE(ferret_adaptive);
     FIELD(ferret_adaptive, lambda); FIELD(ferret_adaptive, v_r); FIELD(ferret_adaptive, v_a);
     FIELD(ferret_adaptive, alpha); FIELD(ferret_adaptive, eta_lambda); FIELD(ferret_adaptive, fused);

@@ -152,6 +152,7 @@ int main(int argc, char **argv) {
         tuned.chunk_bytes = 20000;
         tuned.resident_cap = 3;
         tuned.cache_policy = 2;
+        tuned.xcd_group = 5;
         tuned.slot_align_elems = 1024;
         tuned.slot_skew_elems = 40;
         for (ferret_precision prec : {FERRET_F32, FERRET_BF16_MASTER_F32})

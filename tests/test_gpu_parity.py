@@ -202,7 +202,9 @@ def test_outputs_do_not_depend_on_optional_outputs_or_grid():
                                 (dict(slot_align_elems=4096, slot_skew_elems=520), False, True),
                                 (dict(resident_cap=3), True, True), (dict(resident_cap=-1, blocks_per_cu=2), True, True),
                                 (dict(cache_policy=1), True, True), (dict(cache_policy=2), True, False),
-                                (dict(cache_policy=2, resident_cap=2), False, True)]:
+                                (dict(cache_policy=2, resident_cap=2), False, True),
+                                (dict(xcd_group=1, cache_policy=2), True, True), (dict(xcd_group=3, cache_policy=2), True, True),
+                                (dict(xcd_group=16), True, False), (dict(xcd_group=64, resident_cap=3), True, True)]:
         plan, st, host = PU.load_workload(w, amplified=True, tuning=tuning)
         st.step(w.lam, w.lr, norms=norms, grad_out=gout)
         torch.cuda.synchronize()
@@ -465,7 +467,8 @@ def test_random_configurations(seed):
     chunk = int(rng.choice([0, 1024, 3072, 8192]))
     tuning = [None, dict(blocks_per_cu=2), dict(resident_cap=2), dict(blocks_per_cu=-1, resident_cap=-1),
               dict(cache_policy=2), dict(chunk_bytes=int(rng.choice([1, 20_000, 200_000])), cache_policy=1),
-              dict(cache_policy=2, resident_cap=3)][seed % 7]
+              dict(cache_policy=2, resident_cap=3), dict(xcd_group=int(rng.choice([2, 5, 16])), cache_policy=2),
+              dict(xcd_group=int(rng.choice([1, 3, 40])))][seed % 9]
     if tuning and "chunk_bytes" in tuning:
         chunk = 0                                   # a byte target and an explicit size exclude each other
     w = W.custom_workload(f"random{seed}", sizes, tau, R, K, precision=precision, seed=2000 + seed,

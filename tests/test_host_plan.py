@@ -279,6 +279,7 @@ def test_tuning_validation(lib):
     assert "resident_cap" in bad(resident_cap=1)              # one workgroup cannot hold more than 64 of 160 KiB
     assert "resident_cap" in bad(resident_cap=33)
     assert "cache_policy" in bad(cache_policy=3)
+    assert "xcd_group" in bad(xcd_group=-1) and "xcd_group" in bad(xcd_group=5000)
     assert "chunk_bytes" in bad(chunk_bytes=-1)
     assert "not both" in bad(chunk_bytes=4096, chunk=1024)
     assert "persistent" in bad(newest_from_master=1, blocks_per_cu=2, prec=B.FERRET_BF16_MASTER_F32)
@@ -286,7 +287,7 @@ def test_tuning_validation(lib):
     with pytest.raises(ValueError):
         _plan([[4096]], [1], R=2, tuning=dict(no_such_field=1))
     for ok in (dict(resident_cap=2), dict(resident_cap=-1), dict(cache_policy=1), dict(cache_policy=2),
-               dict(chunk_bytes=1), dict(chunk_bytes=1 << 30)):
+               dict(chunk_bytes=1), dict(chunk_bytes=1 << 30), dict(xcd_group=1), dict(xcd_group=16)):
         plan, _ = _plan([[4096]], [1], R=2, tuning=ok)
         assert plan.n_chunks >= 1 and plan.stage_chunk_elems(0) % 1024 == 0
 
