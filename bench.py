@@ -412,6 +412,8 @@ def main():
                     help="size every stage's chunks so that one chunk moves about this many bytes (sweeps)")
     ap.add_argument("--cache-policy", type=int, default=0, choices=[0, 1, 2],
                     help="0 by working-set size, 1 cached accesses where available, 2 non-temporal (sweeps)")
+    ap.add_argument("--xcd-group", type=int, default=0,
+                    help="consecutive chunks per XCD (ferret_tuning.xcd_group: 0 library default, 1 plain order)")
     ap.add_argument("--slot-align", type=int, default=0)
     ap.add_argument("--slot-skew", type=int, default=0)
     ap.add_argument("--iters", type=int, default=None, help="override K (-1 = one iteration per version step)")
@@ -470,11 +472,11 @@ def main():
         return per_tensor_contrast(w, args, torch, B, W)
     tuning = None
     tuned = bool(args.blocks_per_cu or args.slot_align or args.slot_skew or args.newest_from_master or args.resident_cap
-                 or args.chunk_bytes or args.cache_policy)
+                 or args.chunk_bytes or args.cache_policy or args.xcd_group)
     if tuned:
         tuning = dict(blocks_per_cu=args.blocks_per_cu, slot_align_elems=args.slot_align, resident_cap=args.resident_cap,
                       slot_skew_elems=args.slot_skew, newest_from_master=int(args.newest_from_master),
-                      chunk_bytes=args.chunk_bytes, cache_policy=args.cache_policy)
+                      chunk_bytes=args.chunk_bytes, cache_policy=args.cache_policy, xcd_group=args.xcd_group)
     tuned = tuned or bool(args.chunk_elems) or args.precision is not None
     mode = Mode(adaptive=args.adaptive, fused=args.adaptive_fused, accumulate=args.accumulate,
                 compensator=args.compensator, graph=args.graph, norms=not args.no_norms,
