@@ -1113,10 +1113,15 @@ static uint32_t reserve_lds_for_cap(const ferret_plan &plan, const StepArgs &a, 
             for (uint32_t k = i; k > 0 && block[order[k]] < block[order[k - 1]]; --k) {
                 const uint32_t t = order[k]; order[k] = order[k - 1]; order[k - 1] = t;
             }
+        // With the lambda block fused in, the stage at the 40 % point instead: a cap too low for the lighter chunks
+        // costs more than one too high for the heavier ones (measured at the ViT-B-sized workload with one iteration
+        // per version step, where 45 % of the traffic is in chunks of <= 52 KiB and the rest in 64-88 KiB: cap 3
+        // 605 us, cap 2 643 us; with K <= 5 all heavy stages share one chunk size and either point gives cap 2).
+        const uint64_t point = a.fused_lambda ? 4u : 5u;      // tenths of the traffic
         uint64_t seen = 0, block_bytes = block[order[n - 1]];
         for (uint32_t i = 0; i < n; ++i) {
             seen += traffic[order[i]];
-            if (2 * seen >= total) { block_bytes = block[order[i]]; break; }
+            if (10 * seen >= point * total) { block_bytes = block[order[i]]; break; }
         }
         // the traffic-weighted median of K' itself: the smallest k with at least half the traffic in stages of K' <= k
         for (uint32_t k = 0; *median_kp < 0; ++k) {
