@@ -1131,7 +1131,12 @@ static uint32_t reserve_lds_for_cap(const ferret_plan &plan, const StepArgs &a, 
         }
         if (cap == 0) {
             cap = (int32_t)((kInFlightTargetBytes + block_bytes - 1) / block_bytes);
-            if (cap < 2) cap = 2;
+            // Two resident workgroups are the optimum only with the lambda block fused in (its three write streams);
+            // wherever the rule above says 2 for another launch, 3 measured the same or better: fp32 K = 5 383 -> 380 us,
+            // accumulation at K = 1 294 -> 275 (arrivals that only add) and 340 -> 335 (arrivals that update), bf16
+            // K = 8 1556 -> 1487, bf16 accumulation with one iteration per version step 2063 -> 1692 and 2456 -> 2141.
+            const int32_t floor_cap = a.fused_lambda ? 2 : 3;
+            if (cap < floor_cap) cap = floor_cap;
             if (cap >= 8) return 0;                           // 8 fit anyway
         }
     }
