@@ -560,7 +560,7 @@ def main():
         st_full.__dict__.update(st.__dict__)
         st_full.plan = plan_full
         st_full.workspace = torch.zeros(max(plan_full.workspace_bytes // 4, 4), dtype=torch.float32, device=dev)
-        for mo, key in ((Mode(), w.name + "_full_iterations"), (Mode(fused=True), None)):
+        for mo, key in ((Mode(), w.name + "_full_iterations"), (Mode(adaptive=True), None), (Mode(fused=True), None)):
             record(w_full, mo, measure(torch, B, w_full, plan_full, st_full, mo, args.steps, args.warmup), key)
         del st_full, st, plan_full
         torch.cuda.empty_cache()

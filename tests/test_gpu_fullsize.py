@@ -3,7 +3,7 @@
 
   ViT-B-sized, fp32 (86.6 M parameters, 8 stages)
       one iteration per version step (Alg. 1 literally; the K' <= 8 kernels under the cap)
-      the same with the self-tuned lambda in the one-pass order (Alg. 1's block fused into the step)
+      the same with the self-tuned lambda: Alg. 1 as printed, and its block fused into the step (one pass)
       gradient accumulation with c^a = 2 (T2 in Sec. "Fine-grained Pipeline Parallelism")
   350 M parameters, bf16 versions + fp32 master, 16 stages
       one iteration per version step (K' up to 15: the streamed kernels under the cap), amplified inputs
@@ -95,16 +95,18 @@ def test_vit_b_one_iteration_per_version_step(vit_amplified):
     L.restore(plan)
 
 
-def test_vit_b_one_pass_self_tuned_lambda_with_one_iteration_per_version_step(vit_amplified):
-    """bench.py --adaptive-fused --iters -1: the lambda block fused into a step whose stages have K' = 7 ... 0."""
+@pytest.mark.parametrize("fused", [False, True])
+def test_vit_b_self_tuned_lambda_with_one_iteration_per_version_step(vit_amplified, fused):
+    """bench.py --adaptive / --adaptive-fused with --iters -1: Alg. 1 as printed (the lambda block, then one iteration
+    per version step, stages with K' = 7 ... 0), and the same with the block fused into the step."""
     L = vit_amplified
     w = L.w
     plan = L.plan_like(n_iters=B.FERRET_ITERS_FULL)
     st = L.state_for(plan)
     state = adaptive_state(w, st, 36, w.lam)
-    st.step_adaptive(0.9, 1e-5, w.lr, fused=True)
+    st.step_adaptive(0.9, 1e-5, w.lr, fused=fused)
     torch.cuda.synchronize()
-    check_adaptive(w, plan, st, L.host, state, [w.lam] * w.n_stages, 0.9, 1e-5, -1, "vit full iterations", True,
+    check_adaptive(w, plan, st, L.host, state, [w.lam] * w.n_stages, 0.9, 1e-5, -1, "vit full iterations", fused,
                    n_threads=8)
     L.restore(plan)         # the averages and lambda live on `st`, a view of the buffers that ends here
 
