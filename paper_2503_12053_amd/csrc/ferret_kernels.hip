@@ -1099,7 +1099,17 @@ static uint32_t reserve_lds_for_cap(const ferret_plan &plan, const StepArgs &a, 
             uint64_t per = (uint64_t)inflight_bytes_per_elem(plan.prec, (int32_t)kp);
             if (kp == 0 && a.stage[j].tau > 0 && (a.partials || a.penalized)) per += sb;   // V[0] for the gap
             if (a.fused_lambda && a.stage[j].tau > 0) per += sb + 8;   // V[1], v_r, v_a
-            if (a.accum) per += 8 - sb;     // running sum read + written; most arrivals write no version (measured: 3 at K' = 3)
+            if (a.accum) {
+                if (a.mode[j] == 2) {
+                    per += 8 - sb;          // an arrival that updates: the running sum read and cleared as well
+                } else {
+                    // an arrival that only adds writes no version and touches no master; what it loads together is the
+                    // gradient, the versions and the running sum (measured: 350 M parameters in bf16, K = 4, 1190 us at
+                    // 3 resident workgroups, 1101 at the 4 this gives; fp32 K = 1 and K = 3 stay at their optimum, 3)
+                    const uint64_t versions = kp <= (uint32_t)kUnrolledItersMax ? kp + 1u : (uint32_t)kStreamBatch;
+                    per = sb * (versions + 1u) + 4u;
+                }
+            }
             block[n] = per * a.stage[j].chunk_elems;
             traffic[n] = a.stage[j].n_elems * (sb * (kp + 3u) + (plan.prec == FERRET_F32 ? 0u : 8u) +
                                                (a.fused_lambda && a.stage[j].tau > 0 ? sb + 16u : 0u));
