@@ -387,11 +387,12 @@ def traffic_key(w_name, mode, iters, tuned):
         return None
     if mode.accumulate:
         return w_name + "_accumulate2" if iters is None and mode.accumulate == 2 else None
+    base = w_name + ("_full_iterations" if iters == -1 else "")
     if mode.fused:
-        return w_name + "_one_pass_lambda" if iters is None else None
+        return base + "_one_pass_lambda"
     if mode.adaptive:
-        return None
-    return w_name + ("_full_iterations" if iters == -1 else "")
+        return base + "_adaptive"
+    return base
 
 
 def main():
@@ -548,7 +549,7 @@ def main():
             others.append(rec)
 
         # the same buffers in the other headline modes of the ViT-B-sized workload
-        for mo, key in ((Mode(adaptive=True), None), (Mode(fused=True), w.name + "_one_pass_lambda"),
+        for mo, key in ((Mode(adaptive=True), w.name + "_adaptive"), (Mode(fused=True), w.name + "_one_pass_lambda"),
                         (Mode(accumulate=2), w.name + "_accumulate2")):
             record(w, mo, measure(torch, B, w, plan, st, mo, args.steps, args.warmup), key)
         # Alg. 1 literally: one iteration per version step (another plan over the same buffers: the layout is the same)
@@ -560,7 +561,8 @@ def main():
         st_full.__dict__.update(st.__dict__)
         st_full.plan = plan_full
         st_full.workspace = torch.zeros(max(plan_full.workspace_bytes // 4, 4), dtype=torch.float32, device=dev)
-        for mo, key in ((Mode(), w.name + "_full_iterations"), (Mode(adaptive=True), None), (Mode(fused=True), None)):
+        for mo, key in ((Mode(), w.name + "_full_iterations"), (Mode(adaptive=True), w.name + "_full_iterations_adaptive"),
+                        (Mode(fused=True), w.name + "_full_iterations_one_pass_lambda")):
             record(w_full, mo, measure(torch, B, w_full, plan_full, st_full, mo, args.steps, args.warmup), key)
         del st_full, st, plan_full
         torch.cuda.empty_cache()
@@ -579,7 +581,8 @@ def main():
             extra = {"cpu_baseline": cpu_baseline(w5, host5, plan5, budget_s=10.0)}
             log("cpu baseline:", extra["cpu_baseline"]["sample"])
         record(w5, Mode(), m5, w5.name, extra)
-        record(w5, Mode(fused=True), measure(torch, B, w5, plan5, st5, Mode(fused=True), steps5, 3), None)
+        record(w5, Mode(fused=True), measure(torch, B, w5, plan5, st5, Mode(fused=True), steps5, 3),
+               w5.name + "_one_pass_lambda")
         result["others"] = others
     print(json.dumps(result), flush=True)
 
